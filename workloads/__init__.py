@@ -1,0 +1,135 @@
+"""Seeded synthetic attention inputs (shared by tests, smoke and bench).
+
+This module holds no arithmetic of the attention method itself: it draws real
+tensors from a seed, quantises them per tensor to int8 (Eq. 1-2: symmetric,
+scale = max|x| / 127) and, for the windowed workload, builds the additive
+integer bias / exclusion mask.  Both the CPU oracle and the GPU library are fed
+the arrays made here; neither imports this module.
+
+The five named workloads stand in for the attention layers of ViT / DeiT / Swin
+models (shapes of Table 1, scaled to the batch sizes of the benchmark): real
+activations would need ImageNet and trained weights, which are not available.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+EXCLUDED = np.iinfo(np.int32).min
+
+
+@dataclass
+class Workload:
+    name: str
+    Q: np.ndarray                 # int8 [B,H,N,d]
+    K: np.ndarray
+    V: np.ndarray
+    sQ: float
+    sK: float
+    sV: float
+    kv_tiles: tuple               # KV tile sizes this workload is run with
+    bias: Optional[np.ndarray] = None        # int32 [bias_B,bias_H,N,N] or None
+    bias_real: Optional[np.ndarray] = None   # float64, same shape, 0 where excluded
+    excluded: Optional[np.ndarray] = None    # bool, same shape
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def shape(self):
+        return self.Q.shape
+
+
+def quantize_per_tensor(x: np.ndarray):
+    """Eq. 1-2 with b = 8: s = max|x| / 127 (double), x_hat = clip(rint(x / s), -127, 127)."""
+    amax = float(np.max(np.abs(x)))
+    if amax == 0.0:
+        return np.zeros(x.shape, dtype=np.int8), 1.0
+    s = amax / 127.0
+    q = np.clip(np.rint(x.astype(np.float64) / s), -127, 127).astype(np.int8)
+    return q, s
+
+
+def _draw(rng, shape, dist, sigma=1.0, outlier_frac=0.0, outlier_gain=8.0):
+    if dist == "normal":
+        x = rng.standard_normal(size=shape, dtype=np.float32) * np.float32(sigma)
+    elif dist == "student_t3":
+        x = rng.standard_t(3.0, size=shape).astype(np.float32)
+    else:
+        raise ValueError(dist)
+    if outlier_frac > 0.0:
+        B, H, N, d = shape
+        n_out = int(np.ceil(outlier_frac * H * d))
+        ch = rng.choice(H * d, size=n_out, replace=False)
+        xv = x.transpose(0, 2, 1, 3).reshape(B, N, H * d)    # channel = h*d + t
+        xv[:, :, ch] *= np.float32(outlier_gain)
+        x = xv.reshape(B, N, H, d).transpose(0, 2, 1, 3).copy()
+    return x
+
+
+def make_qkv(shape, seed, dist="normal", sigma=1.0, outlier_frac=0.0):
+    """Q, K, V drawn in that order from one generator, each quantised per tensor."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(3):
+        x = _draw(rng, shape, dist, sigma, outlier_frac)
+        out.append(quantize_per_tensor(x))
+    (Q, sQ), (K, sK), (V, sV) = out
+    return Q, K, V, sQ, sK, sV, rng
+
+
+def swin_window_bias(rng, heads, d, sQ, sK, n_windows=64, win=7):
+    """Relative-position bias plus shifted-window exclusion mask, in units of the int32 score.
+
+    Table [heads, (2*win-1)^2] ~ N(0, 0.5^2), gathered with index
+    (dy + win-1) * (2*win-1) + (dx + win-1).  Windows with an odd index carry the
+    shifted-window mask: the window is split into four regions at row/column
+    win - win//2; a query and a key in different regions exclude each other.
+    Real bias -> integer: round(bias * sqrt(d) / (sQ*sK)), the unit of Q_hat K_hat^T.
+    """
+    n = win * win
+    table = rng.standard_normal(size=(heads, (2 * win - 1) ** 2)) * 0.5
+    ys, xs = np.divmod(np.arange(n), win)
+    dy = ys[:, None] - ys[None, :] + (win - 1)
+    dx = xs[:, None] - xs[None, :] + (win - 1)
+    rel = table[:, dy * (2 * win - 1) + dx]                       # [heads, n, n]
+    split = win - win // 2
+    label = (ys >= split).astype(np.int64) * 2 + (xs >= split).astype(np.int64)
+    differ = label[:, None] != label[None, :]
+    excluded = np.zeros((n_windows, heads, n, n), dtype=bool)
+    excluded[1::2] = differ[None, None]
+    bias_real = np.broadcast_to(rel[None], (n_windows, heads, n, n)).copy()
+    unit = (sQ * sK) / np.sqrt(float(d))
+    bias_int = np.floor(bias_real / unit + 0.5).astype(np.int64)
+    assert np.abs(bias_int).max() < (1 << 20)
+    bias = np.where(excluded, np.int64(EXCLUDED), bias_int).astype(np.int32)
+    bias_real = np.where(excluded, 0.0, bias_int * unit)
+    return bias, bias_real, excluded
+
+
+# name -> (shape [B,H,N,d], dist, sigma, outlier_frac, kv_tiles, windowed)
+CONFIGS = {
+    "deit_tiny_b1":   ((1, 3, 197, 64),   "normal",     1.0, 0.0,  (64,),     False),
+    "vit_b16_b64":    ((64, 12, 197, 64), "normal",     1.0, 0.0,  (64,),     False),
+    "deit_b384_b32":  ((32, 12, 577, 64), "normal",     1.5, 0.0,  (64, 128), False),
+    "swin_t_s1_b64":  ((4096, 3, 49, 32), "normal",     1.0, 0.0,  (64,),     True),
+    "vit_l384_heavy": ((16, 16, 577, 64), "student_t3", 1.0, 0.01, (64,),     False),
+}
+CONFIG_ORDER = list(CONFIGS)
+HEADLINE = "vit_b16_b64"
+
+
+def make_workload(name: str, batch: Optional[int] = None) -> Workload:
+    """Build one of the five named workloads; ``batch`` overrides B (tests use smaller ones).
+
+    Seed = 1000 + position of the workload in CONFIG_ORDER (1-based).
+    """
+    shape, dist, sigma, ofrac, kv_tiles, windowed = CONFIGS[name]
+    if batch is not None:
+        shape = (int(batch),) + tuple(shape[1:])
+    seed = 1000 + CONFIG_ORDER.index(name) + 1
+    Q, K, V, sQ, sK, sV, rng = make_qkv(shape, seed, dist, sigma, ofrac)
+    wl = Workload(name, Q, K, V, sQ, sK, sV, kv_tiles, meta={"seed": seed, "dist": dist})
+    if windowed:
+        wl.bias, wl.bias_real, wl.excluded = swin_window_bias(rng, shape[1], shape[3], sQ, sK)
+    return wl
