@@ -1,0 +1,114 @@
+/*
+ * qflash.h -- C ABI of the MI355X (gfx950) integer-only fused attention forward library.
+ *
+ * The library computes Algorithm 1 ("QFlash") of arxiv 2604.25306: tile-wise attention on int8
+ * Q, K, V with an online softmax carried out entirely in integers (Algorithm 2, the division-free
+ * base-2 exponential; Eq. 9-10 requantisation; ScaleRelease of Appendix B.1; integer
+ * normalisation, Section 4.7).  Output is int8 with scale s_O = s_V (Algorithm 1, Return).
+ *
+ * Conventions for every function:
+ *   - returns QFLASH_OK (0) or a negative QFLASH_ERR_* code; never throws, aborts or synchronises;
+ *   - "device" pointers are HIP device memory on the context's GPU, "host" pointers ordinary memory;
+ *   - the caller owns every buffer it passes; the library owns only the opaque context.
+ */
+#ifndef QFLASH_H
+#define QFLASH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QFLASH_OK           0
+#define QFLASH_ERR_NULL    (-1)  /* a required pointer is NULL                                   */
+#define QFLASH_ERR_SHAPE   (-2)  /* B,H,N,d or the bias extents are outside the supported range  */
+#define QFLASH_ERR_TILE    (-3)  /* kv_tile is not 64 or 128                                      */
+#define QFLASH_ERR_PARAM   (-4)  /* an integer constant in qflash_params is out of range          */
+#define QFLASH_ERR_DEVICE  (-5)  /* no such GPU, not a gfx950, or a HIP runtime error             */
+#define QFLASH_ERR_LAUNCH  (-6)  /* the kernel launch was rejected by the runtime                 */
+#define QFLASH_ERR_CTX     (-7)  /* the context is not a live context of this library             */
+#define QFLASH_ERR_ALIGN   (-8)  /* Q, K, V or O is not 16-byte aligned, bias not 4-byte aligned  */
+
+#define QFLASH_MAX_N       4096  /* 128*127*N must stay below 2^31 with margin                    */
+#define QFLASH_EXCLUDED    INT32_MIN  /* bias value that removes a (query, key) pair              */
+
+typedef struct qflash_ctx qflash_ctx;   /* opaque; created and destroyed by the library */
+
+/*
+ * Integer constants of one call.  They depend only on the real scales and are computed outside
+ * the kernel (Section 4.3 below Eq. 7; Section 4.4 below Eq. 10; Algorithm 1 "Require").
+ * Caller-owned, read during the call only.  With s = sQ*sK*d^(-1/2)*log2(e) (Algorithm 1):
+ */
+typedef struct {
+    int32_t x_shift;    /* k in [0,13]: scores are multiplied by 2^k before Algorithm 2 and s is
+                           divided by 2^k; 0 is the paper as printed, k > 0 keeps s_inv usable when
+                           s is coarse                                                          */
+    int32_t s_inv;      /* round(2^k / s), in [2^10, 2^18)                  (Algorithm 2)         */
+    int32_t exp_mul;    /* M = round(-(s/2^k) * 2^exp_shift), negative      (Algorithm 2)         */
+    int32_t exp_shift;  /* N of q = (x*M) >> N; must be 32                  (Appendix B.2)        */
+    int32_t p_mul;      /* M_r = round(127/s_inv * 2^p_shift)               (Eq. 10)              */
+    int32_t p_shift;    /* r = 8 - floor(log2(127/s_inv))                   (Eq. 9)               */
+    int32_t a_mul;      /* ceil(2^30 / s_inv): brings alpha to 16 fractional bits for ScaleRelease
+                           (Appendix B.1)                                                         */
+    int32_t out_round;  /* 0: floor in the final division (Algorithm 1, last step); 1: nearest    */
+} qflash_params;
+
+/*
+ * Derive every field of *out from the real per-tensor scales of Q and K and the head size d
+ * (host only, no GPU work).  sV does not enter the kernel (it is the output scale) and is only
+ * checked for being positive and finite.  out_round is set to 0.
+ * Errors: NULL, PARAM (scales not positive/finite, or s outside the representable window),
+ * SHAPE (d not 32 or 64).
+ */
+int qflash_params_from_scales(double sQ, double sK, double sV, int d, qflash_params* out /*host*/);
+
+/*
+ * Create a context bound to GPU `device_id`.  *out (host) receives the context.
+ * Errors: NULL, DEVICE (no such device / not gfx950).
+ */
+int qflash_create(qflash_ctx** out, int device_id);
+
+/*
+ * One fused attention forward pass (Algorithm 1), enqueued on `hip_stream`; returns without
+ * waiting for the GPU.
+ *
+ *   Q, K, V  device, int8, [B,H,N,d] contiguous row-major, 16-byte aligned; read only.
+ *   O        device, int8, [B,H,N,d], same layout; every element is written.  Scale s_V.
+ *   bias     device int32 [bias_B,bias_H,N,N] or NULL.  Element [b % bias_B][h % bias_H][i][c] is
+ *            added to the integer score of query i and key c before the row maximum; it is in
+ *            units of the score Q_hat.K_hat (real bias * sqrt(d)/(sQ*sK)).  The value
+ *            QFLASH_EXCLUDED removes the pair: it takes no part in the maximum and gets weight 0.
+ *            Contract: every non-excluded score+bias lies in (-2^21, 2^21) (the initial running
+ *            maximum of Algorithm 1 is -2^21).  A row with every key excluded yields zeros.
+ *            With bias == NULL, bias_B and bias_H are ignored.
+ *   B,H,N,d  1 <= N <= QFLASH_MAX_N, d in {32,64}, B,H >= 1, B*H*N*d < 2^31.
+ *   kv_tile  B_c of Algorithm 1: 64 or 128.  The result depends on it (the running maximum and
+ *            the rescaling of past accumulators happen per KV tile); it does not depend on the
+ *            query block size or on any launch parameter.
+ *   p        host; validated on every call.
+ *   hip_stream  a hipStream_t of the context's device (NULL = the default stream).
+ *
+ * All buffers must stay valid until the stream has executed the work.  Calls on one context
+ * from several host threads are allowed (the context holds no per-call state).
+ * Errors: CTX, NULL, SHAPE, TILE, PARAM, ALIGN, DEVICE, LAUNCH.  On error nothing is enqueued.
+ */
+int qflash_attention(qflash_ctx* ctx,
+                     const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
+                     const int32_t* bias, int bias_B, int bias_H,
+                     int B, int H, int N, int d, int kv_tile,
+                     const qflash_params* p, void* hip_stream);
+
+/*
+ * Destroy a context.  NULL is accepted (returns QFLASH_OK).  Destroying a context twice, or a
+ * pointer that never was a context, returns QFLASH_ERR_CTX and touches nothing.
+ */
+int qflash_destroy(qflash_ctx* ctx);
+
+/* Static, NUL-terminated description of an error code (host). */
+const char* qflash_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QFLASH_H */

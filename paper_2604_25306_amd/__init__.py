@@ -1,0 +1,11 @@
+"""MI355X-native integer-only fused attention (QFlash, arxiv 2604.25306): thin Python binding.
+
+The package is argument marshalling only: every step of the attention runs in the hand-written
+gfx950 kernels of ``libqflash.so`` behind the C ABI declared in ``include/qflash.h``.  There is no
+CPU or PyTorch fallback; if the library has not been built, importing ``binding`` functions raises.
+"""
+from .binding import (  # noqa: F401
+    QFlashError, QFlashParams, Context, library_path, load_library,
+    qflash_params_from_scales, qflash_create, qflash_attention, qflash_destroy, qflash_strerror,
+    EXCLUDED, ERR,
+)

@@ -1,0 +1,146 @@
+"""ctypes binding of the C ABI in include/qflash.h (same names, argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libqflash.so")
+_lib = None
+
+EXCLUDED = -(1 << 31)
+
+ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, "LAUNCH": -6,
+       "CTX": -7, "ALIGN": -8}
+
+EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_attention", "qflash_destroy",
+           "qflash_strerror"]
+
+
+class QFlashError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %d (%s)" % (where, code, qflash_strerror(code)))
+
+
+class QFlashParams(ctypes.Structure):
+    """Mirror of ``qflash_params``."""
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "x_shift", "s_inv", "exp_mul", "exp_shift", "p_mul", "p_shift", "a_mul", "out_round")]
+
+    def astuple(self):
+        return tuple(getattr(self, n) for n, _ in self._fields_)
+
+    def __repr__(self):
+        return "QFlashParams(%s)" % ", ".join("%s=%d" % (n, getattr(self, n)) for n, _ in self._fields_)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libqflash.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                "libqflash.so is missing: build it with `python -m paper_2604_25306_amd.build` "
+                "(hipcc, gfx950). There is no CPU fallback.")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, ci, dbl = ctypes.c_void_p, ctypes.c_int, ctypes.c_double
+        pp = ctypes.POINTER(QFlashParams)
+        lib.qflash_params_from_scales.restype = ci
+        lib.qflash_params_from_scales.argtypes = [dbl, dbl, dbl, ci, pp]
+        lib.qflash_create.restype = ci
+        lib.qflash_create.argtypes = [ctypes.POINTER(vp), ci]
+        lib.qflash_attention.restype = ci
+        lib.qflash_attention.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
+        lib.qflash_destroy.restype = ci
+        lib.qflash_destroy.argtypes = [vp]
+        lib.qflash_strerror.restype = ctypes.c_char_p
+        lib.qflash_strerror.argtypes = [ci]
+        _lib = lib
+    return _lib
+
+
+def qflash_strerror(code: int) -> str:
+    return load_library().qflash_strerror(int(code)).decode()
+
+
+def qflash_params_from_scales(sQ: float, sK: float, sV: float, d: int) -> QFlashParams:
+    p = QFlashParams()
+    rc = load_library().qflash_params_from_scales(float(sQ), float(sK), float(sV), int(d),
+                                                  ctypes.byref(p))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_params_from_scales")
+    return p
+
+
+def qflash_create(device_id: int = 0) -> int:
+    """Returns the opaque context handle (an integer address)."""
+    h = ctypes.c_void_p()
+    rc = load_library().qflash_create(ctypes.byref(h), int(device_id))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_create")
+    return h.value
+
+
+def qflash_destroy(ctx: Optional[int]) -> None:
+    rc = load_library().qflash_destroy(ctypes.c_void_p(ctx))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_destroy")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def qflash_attention(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, bias=None,
+                     stream: Optional[int] = None) -> None:
+    """Enqueue one forward pass.  Q, K, V, O: contiguous int8 CUDA tensors [B,H,N,d];
+    bias: None or contiguous int32 CUDA tensor [bias_B,bias_H,N,N].  ``stream`` is a raw
+    hipStream_t value (default: torch's current stream on the tensors' device)."""
+    import torch
+    for name, t in (("Q", Q), ("K", K), ("V", V), ("O", O)):
+        if t.dtype != torch.int8 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError("%s must be a contiguous int8 CUDA tensor [B,H,N,d]" % name)
+        if t.shape != Q.shape:
+            raise ValueError("Q, K, V, O must share one shape")
+    B, H, N, d = Q.shape
+    bias_B = bias_H = 0
+    if bias is not None:
+        if bias.dtype != torch.int32 or not bias.is_cuda or not bias.is_contiguous() \
+                or bias.dim() != 4 or tuple(bias.shape[2:]) != (N, N):
+            raise ValueError("bias must be a contiguous int32 CUDA tensor [bias_B,bias_H,N,N]")
+        bias_B, bias_H = int(bias.shape[0]), int(bias.shape[1])
+    if stream is None:
+        stream = torch.cuda.current_stream(Q.device).cuda_stream
+    rc = load_library().qflash_attention(
+        ctypes.c_void_p(ctx), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(bias), bias_B, bias_H,
+        int(B), int(H), int(N), int(d), int(kv_tile), ctypes.byref(params),
+        ctypes.c_void_p(stream))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_attention")
+
+
+class Context:
+    """RAII wrapper: ``with Context(0) as ctx: ctx.attention(...)``."""
+
+    def __init__(self, device_id: int = 0):
+        self.handle = qflash_create(device_id)
+
+    def attention(self, Q, K, V, O, params, kv_tile, bias=None, stream=None):
+        qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
+
+    def close(self):
+        if self.handle is not None:
+            qflash_destroy(self.handle)
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

@@ -1,0 +1,200 @@
+// Host side of the C ABI declared in include/qflash.h: argument checking, derivation of the
+// integer constants from the real scales, context bookkeeping, kernel selection.  No arithmetic
+// of the attention itself happens here; all of it runs in the gfx950 kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <set>
+
+#include "qflash.h"
+#include "qflash_internal.h"
+
+struct qflash_ctx {
+    int device;
+};
+
+namespace {
+
+std::mutex g_mu;
+std::set<const qflash_ctx*>& live_contexts() {
+    static std::set<const qflash_ctx*> s;
+    return s;
+}
+
+constexpr int kXShiftMax = 13;
+constexpr int kSInvMin = 1 << 10;
+constexpr int kSInvMax = 1 << 18;  // exclusive
+
+int64_t round_half_up(double x) { return (int64_t)std::floor(x + 0.5); }
+
+// Range and consistency checks that make the 32-bit kernel arithmetic exact (see the comments on
+// x_floor in qflash_internal.h and on shift_exp2 in the kernel source).
+bool params_ok(const qflash_params& p) {
+    if (p.x_shift < 0 || p.x_shift > kXShiftMax) return false;
+    if (p.s_inv < kSInvMin || p.s_inv >= kSInvMax) return false;
+    if (p.exp_shift != 32) return false;
+    if (p.exp_mul >= 0 || p.exp_mul <= -(1 << 23)) return false;
+    // M * s_inv must be -2^32 to within 0.1 %: both come from the same real scale.
+    const int64_t prod = (int64_t)p.exp_mul * (int64_t)p.s_inv + ((int64_t)1 << 32);
+    if (prod > ((int64_t)1 << 32) / 1000 || prod < -(((int64_t)1 << 32) / 1000)) return false;
+    if (p.p_shift < 1 || p.p_shift > 30 || p.p_mul < 1 || p.p_mul >= (1 << 12)) return false;
+    // 1.0 (= s_inv) must requantise to at most 127 so that P fits a signed byte.
+    if ((int64_t)p.s_inv * p.p_mul >= ((int64_t)128 << p.p_shift)) return false;
+    if (p.a_mul < 1 || (int64_t)p.s_inv * p.a_mul >= ((int64_t)1 << 31)) return false;
+    // alpha = 1.0 must map to exactly 2^16 (identity), i.e. s_inv * a_mul >= 2^30.
+    if ((int64_t)p.s_inv * p.a_mul < ((int64_t)1 << 30)) return false;
+    if (p.out_round != 0 && p.out_round != 1) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" int qflash_params_from_scales(double sQ, double sK, double sV, int d, qflash_params* out) {
+    if (!out) return QFLASH_ERR_NULL;
+    if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
+    if (!(sQ > 0.0) || !(sK > 0.0) || !(sV > 0.0) || !std::isfinite(sQ) || !std::isfinite(sK) ||
+        !std::isfinite(sV))
+        return QFLASH_ERR_PARAM;
+    // s = sQ * sK * d^(-1/2) * log2(e), evaluated left to right in double (Algorithm 1, Require).
+    const double log2e = 1.4426950408889634;
+    const double s = ((sQ * sK) / std::sqrt((double)d)) * log2e;
+    if (!(s > 0.0) || !std::isfinite(s)) return QFLASH_ERR_PARAM;
+    int k = 0;
+    while (round_half_up(std::ldexp(1.0, k) / s) < kSInvMin) {
+        if (++k > kXShiftMax) return QFLASH_ERR_PARAM;
+    }
+    const double sk = s / std::ldexp(1.0, k);
+    const int64_t s_inv = round_half_up(1.0 / sk);                 // Algorithm 2: round(1/s)
+    if (s_inv < kSInvMin || s_inv >= kSInvMax) return QFLASH_ERR_PARAM;
+    const int64_t m = round_half_up(-sk * 4294967296.0);           // Algorithm 2: round(-s * 2^N)
+    // Eq. 9: n = floor(log2(127/s_inv)) < 0, found with integers: 2^n <= 127/s_inv < 2^(n+1).
+    int e = 0;
+    while ((int64_t)127 << e < s_inv) ++e;
+    const int r = 8 + e;                                           // r = b - n, b = 8
+    const int64_t m_r = (2 * ((int64_t)127 << r) + s_inv) / (2 * s_inv);   // Eq. 10: round(127/s_inv*2^r)
+    const int64_t a_mul = (((int64_t)1 << 30) + s_inv - 1) / s_inv;
+    qflash_params p;
+    p.x_shift = k;
+    p.s_inv = (int32_t)s_inv;
+    p.exp_mul = (int32_t)m;
+    p.exp_shift = 32;
+    p.p_mul = (int32_t)m_r;
+    p.p_shift = r;
+    p.a_mul = (int32_t)a_mul;
+    p.out_round = 0;
+    if (!params_ok(p)) return QFLASH_ERR_PARAM;
+    *out = p;
+    return QFLASH_OK;
+}
+
+extern "C" int qflash_create(qflash_ctx** out, int device_id) {
+    if (!out) return QFLASH_ERR_NULL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device_id < 0 || device_id >= n) {
+        (void)hipGetLastError();
+        return QFLASH_ERR_DEVICE;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
+        (void)hipGetLastError();
+        return QFLASH_ERR_DEVICE;
+    }
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return QFLASH_ERR_DEVICE;
+    qflash_ctx* c = new (std::nothrow) qflash_ctx;
+    if (!c) return QFLASH_ERR_DEVICE;
+    c->device = device_id;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        live_contexts().insert(c);
+    }
+    *out = c;
+    return QFLASH_OK;
+}
+
+extern "C" int qflash_destroy(qflash_ctx* ctx) {
+    if (!ctx) return QFLASH_OK;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = live_contexts().find(ctx);
+        if (it == live_contexts().end()) return QFLASH_ERR_CTX;
+        live_contexts().erase(it);
+    }
+    delete ctx;
+    return QFLASH_OK;
+}
+
+extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
+                                int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B, int H,
+                                int N, int d, int kv_tile, const qflash_params* p, void* hip_stream) {
+    if (!ctx) return QFLASH_ERR_NULL;
+    int device;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+        device = ctx->device;
+    }
+    if (!Q || !K || !V || !O || !p) return QFLASH_ERR_NULL;
+    if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
+    if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
+    if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+    if (bias) {
+        if (bias_B < 1 || bias_H < 1) return QFLASH_ERR_SHAPE;
+        if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+    }
+    if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
+    if (!params_ok(*p)) return QFLASH_ERR_PARAM;
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
+    if (bias && ((uintptr_t)bias & 3u)) return QFLASH_ERR_ALIGN;
+
+    QflashKernelArgs a;
+    a.Q = Q; a.K = K; a.V = V; a.O = O;
+    a.bias = bias;
+    a.bias_B = bias ? bias_B : 1;
+    a.bias_H = bias ? bias_H : 1;
+    a.B = B; a.H = H; a.N = N;
+    a.x_shift = p->x_shift; a.s_inv = p->s_inv; a.exp_mul = p->exp_mul;
+    a.p_mul = p->p_mul; a.p_shift = p->p_shift; a.a_mul = p->a_mul; a.out_round = p->out_round;
+    // Clamp point of the exponent: smallest multiple of 2^-k at or below -20.5 octaves.
+    // Above it q <= 28 and every intermediate fits 24/32 bits; at and below it the numerator of
+    // Algorithm 2 (< 2^20) is shifted right by >= 20, so the exact result is 0.
+    const int64_t x0 = (41 * (int64_t)p->s_inv + ((int64_t)2 << p->x_shift) - 1) >> (p->x_shift + 1);
+    if ((x0 << p->x_shift) * 2 > 57 * (int64_t)p->s_inv) return QFLASH_ERR_PARAM;  // > 28.5 octaves
+    a.x_floor = (int)-x0;
+    const int rows = qflash_fwd_rows_per_workgroup(d, kv_tile);
+    a.n_qtiles = (N + rows - 1) / rows;
+    const int64_t units = (int64_t)B * H * a.n_qtiles;
+    if (units >= ((int64_t)1 << 30)) return QFLASH_ERR_SHAPE;
+    a.n_units = (int)units;
+    a.units_per_xcd = (a.n_units + 7) / 8;
+
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }
+    if (cur != device && hipSetDevice(device) != hipSuccess) {
+        (void)hipGetLastError();
+        return QFLASH_ERR_DEVICE;
+    }
+    const int rc = qflash_launch_fwd(a, d, kv_tile, hip_stream);
+    if (cur != device) (void)hipSetDevice(cur);
+    if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
+    return QFLASH_OK;
+}
+
+extern "C" const char* qflash_strerror(int code) {
+    switch (code) {
+        case QFLASH_OK: return "success";
+        case QFLASH_ERR_NULL: return "a required pointer is NULL";
+        case QFLASH_ERR_SHAPE: return "unsupported shape (d in {32,64}, 1 <= N <= 4096, sizes below 2^31)";
+        case QFLASH_ERR_TILE: return "kv_tile must be 64 or 128";
+        case QFLASH_ERR_PARAM: return "integer constants out of range or inconsistent";
+        case QFLASH_ERR_DEVICE: return "no such GPU, not a gfx950 device, or HIP runtime error";
+        case QFLASH_ERR_LAUNCH: return "kernel launch failed";
+        case QFLASH_ERR_CTX: return "not a live qflash context";
+        case QFLASH_ERR_ALIGN: return "Q, K, V, O must be 16-byte aligned and bias 4-byte aligned";
+        default: return "unknown qflash error code";
+    }
+}

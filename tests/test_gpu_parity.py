@@ -1,0 +1,243 @@
+"""GPU parity: the HIP library behind the C ABI must reproduce the CPU oracle bit for bit.
+
+All tests here need an MI355X (``-m gpu``).  Inputs are seeded and synthetic; expected values come
+from the oracle run in the same process.  Integer work: the bar is exact equality of every byte.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle.params import OracleParams
+from workloads import make_workload, quantize_per_tensor, EXCLUDED
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2604_25306_amd as qf
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    qf.load_library()                      # raises if the HIP library has not been built
+    ctx = qf.Context(0)
+    yield torch, qf, ctx
+    ctx.close()
+
+
+def lib_params(qf, p: OracleParams):
+    return qf.QFlashParams(*p.astuple())
+
+
+def run_gpu(gpu, Q, K, V, p, tile, bias=None, stream=None):
+    torch, qf, ctx = gpu
+    dev = torch.device("cuda:0")
+    tQ, tK, tV = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (Q, K, V))
+    tO = torch.full(Q.shape, 0x55, dtype=torch.int8, device=dev)
+    tB = torch.from_numpy(np.ascontiguousarray(bias)).to(dev) if bias is not None else None
+    ctx.attention(tQ, tK, tV, tO, lib_params(qf, p), tile, bias=tB, stream=stream)
+    torch.cuda.synchronize()
+    return tO.cpu().numpy()
+
+
+def check(gpu, Q, K, V, p, tile, bias=None, label=""):
+    print("case", label, Q.shape, "tile", tile, "bias", bias is not None, flush=True)
+    ref = oracle.qflash_attention(Q, K, V, p, tile, bias=bias)
+    out = run_gpu(gpu, Q, K, V, p, tile, bias=bias)
+    bad = np.argwhere(out != ref)
+    assert bad.size == 0, "%s: %d mismatches, first at %s: gpu %d oracle %d" % (
+        label, len(bad), bad[0], out[tuple(bad[0])], ref[tuple(bad[0])])
+
+
+def rand_case(shape, seed, sigma=1.0, q_gain=1.0):
+    rng = np.random.default_rng(seed)
+    Qf = rng.standard_normal(shape).astype(np.float32) * np.float32(sigma * q_gain)
+    Kf = rng.standard_normal(shape).astype(np.float32) * np.float32(sigma)
+    Vf = rng.standard_normal(shape).astype(np.float32)
+    (Q, sQ), (K, sK), (V, sV) = (quantize_per_tensor(x) for x in (Qf, Kf, Vf))
+    return Q, K, V, sQ, sK, sV
+
+
+# ------------------------------------------------ shapes: several tiles, ragged tails, extremes
+
+SHAPES = [
+    ((1, 1, 1, 64), 64), ((1, 2, 5, 32), 64), ((2, 2, 31, 64), 64), ((1, 2, 32, 64), 64),
+    ((1, 2, 33, 32), 64), ((2, 1, 64, 64), 64), ((1, 2, 65, 64), 64), ((1, 3, 127, 32), 64),
+    ((1, 2, 128, 64), 128), ((1, 2, 129, 64), 128), ((2, 3, 197, 64), 64), ((1, 2, 197, 64), 128),
+    ((1, 2, 200, 32), 128), ((1, 2, 257, 64), 64), ((1, 2, 300, 32), 64), ((1, 1, 577, 64), 64),
+    ((1, 1, 577, 64), 128), ((1, 1, 1030, 64), 64), ((3, 5, 49, 32), 64), ((3, 5, 49, 32), 128),
+]
+
+
+@pytest.mark.parametrize("idx", range(len(SHAPES)))
+def test_random_shapes(gpu, idx):
+    shape, tile = SHAPES[idx]
+    Q, K, V, sQ, sK, _ = rand_case(shape, 500 + idx, q_gain=1.5)
+    p = oracle.derive_params(sQ, sK, shape[-1])
+    check(gpu, Q, K, V, p, tile, label="random")
+
+
+@pytest.mark.parametrize("out_round", [0, 1])
+def test_out_round(gpu, out_round):
+    Q, K, V, sQ, sK, _ = rand_case((2, 2, 150, 64), 77)
+    p = oracle.derive_params(sQ, sK, 64, out_round=out_round)
+    check(gpu, Q, K, V, p, 64, label="out_round=%d" % out_round)
+
+
+def test_max_n(gpu):
+    Q, K, V, sQ, sK, _ = rand_case((1, 1, 4096, 64), 4096)
+    p = oracle.derive_params(sQ, sK, 64)
+    check(gpu, Q, K, V, p, 128, label="N=4096")
+
+
+# ------------------------------------------------------------------------- adversarial values
+
+
+def test_uniform_scores_and_extreme_values(gpu):
+    rng = np.random.default_rng(1)
+    shape = (1, 2, 197, 64)
+    p = oracle.derive_params(0.04, 0.04, 64)
+    Q = rng.integers(-127, 128, size=shape).astype(np.int8)
+    V = rng.integers(-128, 128, size=shape).astype(np.int8)
+    check(gpu, Q, np.zeros(shape, np.int8), V, p, 64, label="K=0")
+    for qv, kv, vv in ((127, 127, 127), (127, -127, -128), (-128, -128, -128), (-128, 127, 127)):
+        check(gpu, np.full(shape, qv, np.int8), np.full(shape, kv, np.int8),
+              np.full(shape, vv, np.int8), p, 64, label="const %d %d %d" % (qv, kv, vv))
+    signs = rng.choice(np.array([-127, 127], dtype=np.int8), size=(3,) + shape)
+    check(gpu, signs[0], signs[1], signs[2], p, 64, label="all +-127")
+    # worst case for the accumulators at the largest N the 24-bit paths must carry
+    shape = (1, 1, 512, 64)
+    check(gpu, np.zeros(shape, np.int8), np.zeros(shape, np.int8), np.full(shape, -128, np.int8),
+          p, 64, label="max |O| N=512")
+    shape = (1, 1, 4096, 32)
+    check(gpu, np.zeros(shape, np.int8), np.zeros(shape, np.int8), np.full(shape, -128, np.int8),
+          oracle.derive_params(0.04, 0.04, 32), 128, label="max |O| N=4096")
+
+
+def test_outliers_and_sorted_maxima(gpu):
+    Q, K, V, sQ, sK, _ = rand_case((1, 2, 260, 64), 5, q_gain=2.0)
+    p = oracle.derive_params(sQ, sK, 64)
+    K2 = K.copy()
+    K2[:, :, 200] = np.sign(Q[:, :, 7]) * 127            # one huge score late in the sequence
+    check(gpu, Q, K2, V, p, 64, label="late outlier")
+    Qp = np.clip(Q[:, :, :1].astype(np.int64) + np.random.default_rng(2).integers(-3, 4, Q.shape),
+                 -127, 127).astype(np.int8)
+    s0 = Qp[0, 0, 0].astype(np.int64) @ K[0, 0].astype(np.int64).T
+    for name, perm in (("ascending", np.argsort(s0)), ("descending", np.argsort(-s0))):
+        check(gpu, Qp, K[:, :, perm], V[:, :, perm], p, 64, label=name)
+
+
+def test_coarse_and_fine_scales(gpu):
+    """x_shift > 0 (coarse scores) and the largest supported s_inv."""
+    rng = np.random.default_rng(8)
+    shape = (1, 2, 150, 64)
+    Q = rng.integers(-127, 128, size=shape).astype(np.int8)
+    K = rng.integers(-127, 128, size=shape).astype(np.int8)
+    V = rng.integers(-127, 128, size=shape).astype(np.int8)
+    for sQ, sK in ((3.0, 4.0), (0.9, 1.1), (6.0, 7.0), (0.0048, 0.0048), (0.2, 0.2)):
+        p = oracle.derive_params(sQ, sK, 64)
+        check(gpu, Q, K, V, p, 64, label="scales %g %g k=%d s_inv=%d" % (sQ, sK, p.x_shift, p.s_inv))
+    # scaling identity on the GPU as well: forced x_shift
+    base = oracle.derive_params(0.02, 0.02, 64)
+    Ks = rng.integers(-15, 16, size=shape).astype(np.int8)
+    check(gpu, Q, Ks, V, OracleParams(3, *base.astuple()[1:]), 64, label="forced k=3")
+
+
+# ------------------------------------------------------------------------------ bias and mask
+
+
+def test_bias_and_exclusion(gpu):
+    Q, K, V, sQ, sK, _ = rand_case((4, 3, 49, 32), 43, q_gain=1.5)
+    p = oracle.derive_params(sQ, sK, 32)
+    rng = np.random.default_rng(3)
+    bias = rng.integers(-20000, 20000, size=(2, 3, 49, 49)).astype(np.int32)
+    check(gpu, Q, K, V, p, 64, bias=bias, label="bias [2,3]")
+    check(gpu, Q, K, V, p, 64, bias=bias[:1, :1], label="bias [1,1]")
+    mask = rng.random((2, 3, 49, 49)) < 0.3
+    bias_m = np.where(mask, np.int32(EXCLUDED), bias)
+    bias_m[0, 0, 5, :] = EXCLUDED                      # a row with nothing to attend to
+    check(gpu, Q, K, V, p, 64, bias=bias_m, label="bias + mask")
+    # several tiles, d = 64, whole tiles excluded for some rows
+    Q, K, V, sQ, sK, _ = rand_case((2, 2, 200, 64), 44)
+    p = oracle.derive_params(sQ, sK, 64)
+    bias = rng.integers(-3000, 3000, size=(1, 2, 200, 200)).astype(np.int32)
+    bias[0, 0, 10, :64] = EXCLUDED
+    bias[0, 0, 11, 64:128] = EXCLUDED
+    bias[0, 1, 12, :192] = EXCLUDED
+    bias[0, 1, 13, :] = EXCLUDED
+    bias[0, :, :, 199] = EXCLUDED
+    for tile in (64, 128):
+        check(gpu, Q, K, V, p, tile, bias=bias, label="multi-tile mask")
+
+
+# -------------------------------------------- the five benchmark workloads at their full size
+
+
+@pytest.mark.parametrize("name", ["deit_tiny_b1", "vit_b16_b64", "deit_b384_b32", "swin_t_s1_b64",
+                                  "vit_l384_heavy"])
+def test_benchmark_workloads_full_size(gpu, name):
+    """Same launch configuration as bench.py; every output byte is compared (the oracle needs a few
+    seconds per workload on the host cores)."""
+    wl = make_workload(name)
+    p = oracle.derive_params(wl.sQ, wl.sK, wl.shape[-1])
+    if name == "vit_l384_heavy":
+        assert p.x_shift > 0
+    for tile in wl.kv_tiles:
+        check(gpu, wl.Q, wl.K, wl.V, p, tile, bias=wl.bias, label=name)
+
+
+# ------------------------------------------------------------------------------ ABI behaviour
+
+
+def test_stream_determinism_and_full_overwrite(gpu):
+    torch, qf, ctx = gpu
+    Q, K, V, sQ, sK, _ = rand_case((2, 3, 197, 64), 9)
+    p = oracle.derive_params(sQ, sK, 64)
+    ref = oracle.qflash_attention(Q, K, V, p, 64)
+    a = run_gpu(gpu, Q, K, V, p, 64)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        b = run_gpu(gpu, Q, K, V, p, 64)
+    c = run_gpu(gpu, Q, K, V, p, 64, stream=s.cuda_stream)
+    assert np.array_equal(a, ref) and np.array_equal(b, ref) and np.array_equal(c, ref)
+
+
+def test_error_codes_on_gpu(gpu):
+    torch, qf, ctx = gpu
+    lib = qf.load_library()
+    dev = torch.device("cuda:0")
+    t = torch.zeros((1, 1, 64, 64), dtype=torch.int8, device=dev)
+    o = torch.zeros_like(t)
+    p = qf.qflash_params_from_scales(0.04, 0.04, 0.04, 64)
+    h = ctypes.c_void_p(ctx.handle)
+    ptr = lambda x: ctypes.c_void_p(x.data_ptr())  # noqa: E731
+
+    def call(Qp=None, N=64, d=64, tile=64, par=p, B=1, H=1, bias=None, bB=0, bH=0):
+        return lib.qflash_attention(h, Qp if Qp is not None else ptr(t), ptr(t), ptr(t), ptr(o), bias,
+                                    bB, bH, B, H, N, d, tile, ctypes.byref(par) if par else None, None)
+
+    assert call() == 0
+    assert call(par=None) == qf.ERR["NULL"]
+    assert call(Qp=ctypes.c_void_p(None)) == qf.ERR["NULL"]
+    assert call(d=48) == qf.ERR["SHAPE"]
+    assert call(N=0) == qf.ERR["SHAPE"]
+    assert call(N=4097) == qf.ERR["SHAPE"]
+    assert call(B=0) == qf.ERR["SHAPE"]
+    assert call(tile=32) == qf.ERR["TILE"]
+    assert call(Qp=ctypes.c_void_p(t.data_ptr() + 4)) == qf.ERR["ALIGN"]
+    assert call(bias=ptr(t), bB=0, bH=1) == qf.ERR["SHAPE"]
+    for field, val in (("s_inv", 100), ("s_inv", 1 << 18), ("x_shift", 14), ("exp_shift", 31),
+                       ("exp_mul", 5), ("p_mul", 0), ("a_mul", 1), ("out_round", 2)):
+        bad = qf.QFlashParams(*p.astuple())
+        setattr(bad, field, val)
+        assert call(par=bad) == qf.ERR["PARAM"], field
+    torch.cuda.synchronize()
+    # context life cycle
+    h2 = qf.qflash_create(0)
+    qf.qflash_destroy(h2)
+    assert lib.qflash_destroy(ctypes.c_void_p(h2)) == qf.ERR["CTX"]
+    assert lib.qflash_attention(ctypes.c_void_p(h2), ptr(t), ptr(t), ptr(t), ptr(o), None, 0, 0,
+                                1, 1, 64, 64, 64, ctypes.byref(p), None) == qf.ERR["CTX"]
+    hh = ctypes.c_void_p()
+    assert lib.qflash_create(ctypes.byref(hh), 99) == qf.ERR["DEVICE"]
