@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--workload", default=None)
     ap.add_argument("--kv-tile", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device-to-device copy, so that a rocprofv3 --pmc "
+                         "trace of this command holds a kernel of known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over batch*heads with no "
@@ -85,6 +88,14 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         return wall, ev0.elapsed_time(ev1) * 1e-3
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.int8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
