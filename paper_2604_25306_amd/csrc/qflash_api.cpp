@@ -15,6 +15,7 @@
 
 struct qflash_ctx {
     int device;
+    int lds_limit;   // LDS bytes one workgroup may allocate on this device
 };
 
 namespace {
@@ -108,6 +109,12 @@ extern "C" int qflash_create(qflash_ctx** out, int device_id) {
     qflash_ctx* c = new (std::nothrow) qflash_ctx;
     if (!c) return QFLASH_ERR_DEVICE;
     c->device = device_id;
+    int lds = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device_id) != hipSuccess) {
+        (void)hipGetLastError();
+        lds = 64 * 1024;
+    }
+    c->lds_limit = lds;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         live_contexts().insert(c);
@@ -132,11 +139,12 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
                                 int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B, int H,
                                 int N, int d, int kv_tile, const qflash_params* p, void* hip_stream) {
     if (!ctx) return QFLASH_ERR_NULL;
-    int device;
+    int device, lds_limit;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
         device = ctx->device;
+        lds_limit = ctx->lds_limit;
     }
     if (!Q || !K || !V || !O || !p) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
@@ -165,8 +173,7 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
     const int64_t x0 = (41 * (int64_t)p->s_inv + ((int64_t)2 << p->x_shift) - 1) >> (p->x_shift + 1);
     if ((x0 << p->x_shift) * 2 > 57 * (int64_t)p->s_inv) return QFLASH_ERR_PARAM;  // > 28.5 octaves
     a.x_floor = (int)-x0;
-    const int rows = qflash_fwd_rows_per_workgroup(d, kv_tile);
-    a.n_qtiles = (N + rows - 1) / rows;
+    qflash_plan_fwd(N, d, kv_tile, lds_limit, &a);
     const int64_t units = (int64_t)B * H * a.n_qtiles;
     if (units >= ((int64_t)1 << 30)) return QFLASH_ERR_SHAPE;
     a.n_units = (int)units;
@@ -178,7 +185,7 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
         (void)hipGetLastError();
         return QFLASH_ERR_DEVICE;
     }
-    const int rc = qflash_launch_fwd(a, d, kv_tile, hip_stream);
+    const int rc = qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
     return QFLASH_OK;

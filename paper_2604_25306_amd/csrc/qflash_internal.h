@@ -17,11 +17,12 @@ struct QflashKernelArgs {
     int x_floor;
     // work decomposition: one unit = (batch*head, query tile); XCD x owns units
     // [x*units_per_xcd, (x+1)*units_per_xcd)
-    int n_qtiles, n_units, units_per_xcd;
+    int rows_per_wg, n_qtiles, n_units, units_per_xcd;
 };
 
 // Enqueue the forward kernel for head size d (32|64), KV tile (64|128).  Returns a hipError_t value.
-int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, void* stream);
+int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 
-// Rows of Q handled by one workgroup of the forward kernel.
-int qflash_fwd_rows_per_workgroup(int d, int kv_tile);
+// Choose the kernel variant for a head of N rows and fill rows_per_wg and n_qtiles.
+// lds_limit = LDS bytes one workgroup may use on this device.
+int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);

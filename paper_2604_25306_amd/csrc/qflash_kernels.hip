@@ -1,10 +1,5 @@
 // gfx950 (CDNA4) kernels of the integer-only fused attention forward pass (Algorithm 1).
 //
-// Work decomposition
-//   One workgroup = 4 wavefronts = one (batch, head) and 128 consecutive query rows; each
-//   wavefront owns 32 query rows for the whole kernel.  KV tiles of B_c rows are staged through
-//   LDS once per workgroup and shared by its four wavefronts.
-//
 // Operand layout (the point of the design)
 //   Both products are computed transposed on the 32x32x32 int8 MFMA:
 //       S^T = K_j Q_i^T        (A = K rows, B = Q rows)          -> C[kv][query]
@@ -12,12 +7,23 @@
 //   In the MFMA result layout lane l holds column (l % 32) and 16 rows, so every lane owns ONE
 //   query row: 16 of each 32 scores of that row (the other 16 sit in lane l^32), its running
 //   maximum, denominator and alpha, and 16 of each 32 output features.  The row maximum and row
-//   sum are 15 in-lane operations plus a single exchange with lane l^32, alpha is a per-lane
+//   sum are in-lane operations plus a single exchange with lane l^32, alpha is a per-lane
 //   scalar, and the four dwords of int8 weights a lane produces are, unchanged, its B operand of
 //   the second product: P never leaves registers.  The price is that the k-slots of that operand
 //   enumerate the kv rows in result-layout order (8*(j/4) + 4*(l/32) + j%4), so V^T is written to
 //   LDS with its columns in exactly that order.  Integer addition is associative, so the order of
 //   the contraction does not change a single bit of the result.
+//
+// Two kernels share the per-tile code:
+//   resident  one workgroup = one (batch, head) and up to 16 wavefronts of 32 query rows; the
+//             whole K and V^T of the head are staged in LDS once (N up to about 1100), after
+//             which the wavefronts run independently, with no barrier in the KV loop.
+//   stream    one workgroup = 128 query rows; KV tiles are staged per iteration (any N).
+//
+// The element-wise integer softmax is the binding resource (about ten VALU operations per score
+// against 256 MFMA operations and 1.3 HBM bytes), so the per-element path is written for the
+// full-rate 24-bit multiplier (v_mul_hi_i32_i24, v_mad_i32_i24) and packs its int8 result with an
+// SDWA byte write instead of separate shift/or operations.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,62 +34,370 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
-constexpr int kRowsPerWave = 32;
-constexpr int kRowsPerWg = kWaves * kRowsPerWave;
 constexpr int kNegBig = -(1 << 30);   // stands for "excluded": far below any clamp point
 constexpr int kMInit = -(1 << 21);    // initial running maximum (Algorithm 1)
+
+// ------------------------------------------------------------------ scalar building blocks
 
 // (a * b) >> 32 for operands that fit 24 signed bits: one full-rate v_mul_hi_i32_i24.
 __device__ __forceinline__ int mulhi24(int a, int b) {
     const int a24 = (a << 8) >> 8, b24 = (b << 8) >> 8;
     return (int)(((long long)a24 * (long long)b24) >> 32);
 }
+// (a * b) >> 32 for operands below 2^24: v_mul_hi_u32_u24.
+__device__ __forceinline__ unsigned umulhi24(unsigned a, unsigned b) {
+    return (unsigned)(((unsigned long long)(a & 0xffffffu) * (unsigned long long)(b & 0xffffffu)) >> 32);
+}
+// packed.byte[B] = (v >> sh) & 0xff, other bytes kept: the shift and the byte insert are one
+// SDWA instruction.  The caller guarantees (v >> sh) < 256.
+template <int B>
+__device__ __forceinline__ unsigned shr_into_byte(unsigned packed, unsigned sh, unsigned v) {
+    if (B == 0) return v >> sh;
+    if (B == 1)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(sh), "v"(v));
+    if (B == 2)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(sh), "v"(v));
+    if (B == 3)
+        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+            : "+v"(packed) : "v"(sh), "v"(v));
+    return packed;
+}
 
-// Algorithm 2 for an argument already clamped to [x_floor, 0].  With x' = x << k:
-//   q = (x' * M) >> 32,  r = x' + q * s_inv,  y = ((r >> 1) + s_inv) >> q.
+// Exchange with the lane that holds the other half of the same query row.
+__device__ __forceinline__ int other_half(int v) { return __shfl_xor(v, 32, 64); }
+
+// Loop-invariant constants of Algorithm 2 / Eq. 10 kept in registers.
+struct ExpConst {
+    int k, s_inv, two_s_inv, M, p_mul, x_floor;
+    unsigned p_shift;
+};
+
+// Algorithm 2 for a score t already clamped from below to (m + x_floor); neg_m = -m.
+//   x' = (t - m) << k,  q = (x' * M) >> 32,  r = x' + q * s_inv,  y = ((r >> 1) + s_inv) >> q.
 // (r >> 1) + s_inv = floor((r + 2 s_inv) / 2) and nested floors of divisions by powers of two
 // compose, so y = (r + 2 s_inv) >> (q + 1).  In the clamped range x' fits 24 bits, 0 <= q <= 28
 // and r + 2 s_inv is positive, so the logical shift is exact.
-__device__ __forceinline__ int shift_exp2(int x, const QflashKernelArgs& a) {
-    const int xs = x << a.x_shift;
-    const int q = mulhi24(xs, a.exp_mul);
-    const int r2 = __mul24(q, a.s_inv) + xs + 2 * a.s_inv;
+__device__ __forceinline__ int shift_exp2(int t, int neg_m, const ExpConst& c) {
+    const int xs = (t + neg_m) << c.k;
+    const int q = mulhi24(xs, c.M);
+    const int r2 = __mul24(q, c.s_inv) + xs + c.two_s_inv;
     return (int)((unsigned)r2 >> (q + 1));
 }
 
-// Eq. 10: int32 -> [0,127].  y <= s_inv and s_inv * p_mul < 128 << p_shift (checked on the host).
-__device__ __forceinline__ int requant(int y, const QflashKernelArgs& a) {
-    return (int)((unsigned)__mul24(y, a.p_mul) >> a.p_shift);
-}
-
 // ScaleRelease with alpha in 16 fractional bits: floor(x * alpha16 / 2^16).
+// NARROW: |x| < 2^23, three full-rate operations.  Otherwise |x| < 2^26: (x*2^5 * a*2^11) >> 32.
+template <bool NARROW>
 __device__ __forceinline__ int scale_release(int x, int alpha16) {
-    return (int)(((long long)x * (long long)alpha16) >> 16);
+    if (NARROW) {
+        const int hi = mulhi24(x, alpha16);
+        const unsigned lo = (unsigned)__mul24(x, alpha16);
+        return (int)__builtin_amdgcn_alignbit((unsigned)hi, lo, 16);
+    }
+    return __mulhi(x << 5, alpha16 << 11);
 }
 
-__device__ __forceinline__ int floor_div_pos(int a, int b) {   // b > 0
-    int q = a / b;
-    if (a - q * b < 0) q -= 1;
-    return q;
+// ceil(2^(2L+8) / d) for d in (2^(L-1), 2^L] by restoring division: integer only, L+9 steps.
+template <int L>
+__device__ __forceinline__ unsigned recip_ceil(unsigned d) {
+    unsigned rem = 1u << (L - 1), q = 0;
+#pragma unroll
+    for (int it = 0; it < L + 9; ++it) {
+        rem <<= 1;
+        const unsigned sub = rem - d;
+        const bool ge = rem >= d;
+        rem = ge ? sub : rem;
+        q = (q << 1) | (ge ? 1u : 0u);
+    }
+    return q + (rem != 0 ? 1u : 0u);
 }
 
-__device__ __forceinline__ int xor32(int v) { return __shfl_xor(v, 32, 64); }
+// ---------------------------------------------------------------------- per-wavefront state
 
-template <int D, int BC, bool BIAS>
-__global__ __launch_bounds__(kThreads) void qflash_fwd_kernel(const QflashKernelArgs a) {
-    constexpr int KSTEPS = D / 32;   // 32-wide steps of the Q.K contraction
-    constexpr int TB = D / 32;       // 32-row blocks of O^T
-    constexpr int KB = BC / 32;      // 32-row kv blocks of one KV tile
-    constexpr int KROW = D + 16;     // LDS row pitch of the K tile in bytes (pad against conflicts)
-    constexpr int VROW = BC + 16;    // LDS row pitch of the transposed V tile
+template <int D>
+struct RowState {
+    v16i acc[D / 32];   // O^T: features 32*t + 8*(v/4) + 4*g + v%4 of this lane's query row
+    int l;              // running denominator
+    int m;              // running maximum
+};
+
+// One KV tile for one wavefront.  sK: K rows of the tile (row pitch KROW), sV: V^T with the tile's
+// columns starting at column 0 (row pitch VROW).  n_valid = number of real kv rows in the tile.
+template <int D, int BC, bool BIAS, bool NARROW>
+__device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
+                                            const int8_t* sV, int VROW, int n_valid, bool first,
+                                            const int32_t* bias_row /* + c0 */, const ExpConst& c,
+                                            int a_mul, int li, int g) {
+    constexpr int KSTEPS = D / 32, TB = D / 32, KB = BC / 32;
+    // ---- step 1: S^T blocks (32 kv rows x 32 queries each)
+    v16i s[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        if (32 * kb < n_valid) {
+            const v4i ka0 = *(const v4i*)(sK + (32 * kb + li) * KROW + 16 * g);
+            s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], v16i{0}, 0, 0, 0);
+#pragma unroll
+            for (int ks = 1; ks < KSTEPS; ++ks) {
+                const v4i ka = *(const v4i*)(sK + (32 * kb + li) * KROW + 32 * ks + 16 * g);
+                s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka, qreg[ks], s[kb], 0, 0, 0);
+            }
+        }
+    }
+    // ---- bias, exclusion and the ragged end of the sequence.  Groups of 4 scores (one result
+    //      dword of P) that lie wholly beyond the sequence are skipped everywhere below: the test
+    //      32*kb + 8*a4 < n_valid is uniform over the wavefront.
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+            const int cb = 32 * kb + 8 * a4;            // first kv row of the group for g = 0
+            if (cb < n_valid && (BIAS || cb + 8 > n_valid)) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int col = cb + 4 * g + b;
+                    int val = s[kb][4 * a4 + b];
+                    bool excl = col >= n_valid;
+                    if (BIAS && !excl) {
+                        const int bv = bias_row[col];
+                        excl = (bv == INT32_MIN);
+                        val += excl ? 0 : bv;
+                    }
+                    s[kb][4 * a4 + b] = excl ? kNegBig : val;
+                }
+            }
+        }
+    // ---- steps 2,3: row maximum over the tile, running maximum
+    int m_new = st.m;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4)
+            if (32 * kb + 8 * a4 < n_valid) {
+                m_new = max(m_new, max(s[kb][4 * a4], s[kb][4 * a4 + 1]));
+                m_new = max(m_new, max(s[kb][4 * a4 + 2], s[kb][4 * a4 + 3]));
+            }
+    m_new = max(m_new, other_half(m_new));
+    const int neg_m = -m_new;
+    const int lo = m_new + c.x_floor;
+    // ---- step 4: max-offset factor alpha, brought to 16 fractional bits
+    int alpha16 = 0;
+    if (!first) {
+        const int a_hat = shift_exp2(max(st.m, lo), neg_m, c);
+        alpha16 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536);
+    }
+    // ---- steps 5,6,7: score intensity, requantisation to int8 (Eq. 10), row sum
+    v4i pk[KB];
+    int rowsum = 0;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        pk[kb] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4)
+            if (32 * kb + 8 * a4 < n_valid) {
+                unsigned w = 0;
+                {
+                    const int y = shift_exp2(max(s[kb][4 * a4 + 0], lo), neg_m, c);
+                    w = shr_into_byte<0>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
+                }
+                {
+                    const int y = shift_exp2(max(s[kb][4 * a4 + 1], lo), neg_m, c);
+                    w = shr_into_byte<1>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
+                }
+                {
+                    const int y = shift_exp2(max(s[kb][4 * a4 + 2], lo), neg_m, c);
+                    w = shr_into_byte<2>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
+                }
+                {
+                    const int y = shift_exp2(max(s[kb][4 * a4 + 3], lo), neg_m, c);
+                    w = shr_into_byte<3>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
+                }
+                pk[kb][a4] = (int)w;
+                rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
+            }
+    }
+    rowsum += other_half(rowsum);
+    // ---- steps 9,10: ScaleRelease of the running denominator and numerator
+    if (first) {
+        st.l = rowsum;
+    } else {
+        st.l = scale_release<NARROW>(st.l, alpha16) + rowsum;
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release<NARROW>(st.acc[t][v], alpha16);
+    }
+    // ---- step 8: O^T += V_j^T P^T
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+            if (32 * kb < n_valid) {
+                const v4i va = *(const v4i*)(sV + (32 * t + li) * VROW + 32 * kb + 16 * g);
+                st.acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], st.acc[t], 0, 0, 0);
+            }
+    st.m = m_new;
+}
+
+// Step 11: integer normalisation floor(O / l) (or nearest), saturated to int8, without a division
+// per element.  With u = O + 128 l clamped to [0, 256 l), t = floor(u / l) lies in [0, 255] and
+// floor(O / l) saturated to [-128, 127] equals t - 128, i.e. byte t ^ 0x80.  l is normalised to
+// l' = l << z in (2^(L-1), 2^L] and R = ceil(2^(2L+8) / l'); then floor(u' R / 2^(2L+8)) is exact
+// for every u' < 256 l' because u' (R l' - 2^(2L+8)) < 2^(L+8) 2^L.
+template <int D, int L>
+__device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* Orow, int g, bool round_nearest) {
+    constexpr int TB = D / 32;
+    // floor((2 O + l) / (2 l)) for nearest: numerator 2 O + l, denominator 2 l
+    const unsigned den = round_nearest ? 2u * (unsigned)st.l : (unsigned)st.l;
+    const bool empty = st.l == 0;
+    const unsigned dsafe = empty ? 1u : den;
+    const int z = L - (32 - __clz((int)(dsafe - 1)));          // dsafe << z in (2^(L-1), 2^L]
+    const unsigned dn = dsafe << z;
+    const unsigned R = recip_ceil<L>(dn);
+    const int bias_u = (int)(128u * dsafe) + (round_nearest ? st.l : 0);
+    const int u_max = (int)(256u * dn) - 1;
+    const int num_mul = round_nearest ? 2 : 1;
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+            unsigned word = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int o = st.acc[t][4 * a4 + b];
+                int u = (o * num_mul + bias_u) << z;
+                u = min(max(u, 0), u_max);
+                unsigned tq;
+                if (L <= 15) tq = umulhi24((unsigned)u, R) >> (2 * L + 8 - 32);
+                else tq = __umulhi((unsigned)u, R) >> (2 * L + 8 - 32);
+                word |= tq << (8 * b);
+            }
+            word ^= 0x80808080u;
+            if (empty) word = 0;
+            *(unsigned*)(Orow + 32 * t + 8 * a4 + 4 * g) = word;
+        }
+}
+
+__device__ __forceinline__ ExpConst make_exp_const(const QflashKernelArgs& a) {
+    ExpConst c;
+    c.k = a.x_shift; c.s_inv = a.s_inv; c.two_s_inv = 2 * a.s_inv; c.M = a.exp_mul;
+    c.p_mul = a.p_mul; c.x_floor = a.x_floor; c.p_shift = (unsigned)a.p_shift;
+    return c;
+}
+
+// V rows [r0, r0+4) x features [16*tq, 16*tq+16) -> V^T in LDS, kv columns in result-layout order.
+// col_base = LDS column of kv row r0's 32-row block start; r_in_blk = r0 % 32 (multiple of 4).
+__device__ __forceinline__ void stage_v_4x16(const int8_t* Vh, int D, int N, int r0, int tq, int8_t* sV, int VROW,
+                                             int lds_col_blk, int r_in_blk) {
+    v4i rw[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        rw[b] = v4i{0, 0, 0, 0};
+        if (r0 + b < N) rw[b] = *(const v4i*)(Vh + (size_t)(r0 + b) * D + 16 * tq);
+    }
+    // kv row 8*a4 + 4*g2 + b of a block  ->  slot 16*g2 + 4*a4 + b
+    const int pos = lds_col_blk + 16 * ((r_in_blk >> 2) & 1) + 4 * (r_in_blk >> 3);
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const unsigned o = (((unsigned)rw[0][w] >> (8 * f)) & 0xffu) | ((((unsigned)rw[1][w] >> (8 * f)) & 0xffu) << 8) |
+                               ((((unsigned)rw[2][w] >> (8 * f)) & 0xffu) << 16) | ((((unsigned)rw[3][w] >> (8 * f)) & 0xffu) << 24);
+            *(unsigned*)(sV + (16 * tq + 4 * w + f) * VROW + pos) = o;
+        }
+}
+
+// ------------------------------------------------------------------------ resident kernel
+
+extern __shared__ __align__(16) int8_t smem[];
+
+template <int D, int BC, bool BIAS, bool NARROW>
+__global__ __launch_bounds__(1024) void qflash_fwd_resident(const QflashKernelArgs a) {
+    constexpr int KSTEPS = D / 32;
+    constexpr int KROW = D + 16;
+    const int N = a.N;
+    const int npad = (N + 31) & ~31;
+    const int VROW = npad + 16;
+    int8_t* sK = smem;                       // [npad][KROW]
+    int8_t* sV = smem + (size_t)npad * KROW; // [D][VROW]
+
+    const int wg = blockIdx.x;
+    const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
+    if (unit >= a.n_units) return;
+    const int qt = unit % a.n_qtiles;
+    const int bh = unit / a.n_qtiles;
+
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, li = lane & 31;
+    const int row0 = qt * a.rows_per_wg + wave * 32;
+    const int i = row0 + li;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const int8_t* Qh = a.Q + head_off;
+    const int8_t* Kh = a.K + head_off;
+    const int8_t* Vh = a.V + head_off;
+
+    // ---- stage the whole K (row-major) and V^T (permuted columns) of this head
+    for (int ch = tid; ch < npad * (D / 16); ch += nthr) {
+        const int r = ch / (D / 16), c16 = ch % (D / 16);
+        v4i val = {0, 0, 0, 0};
+        if (r < N) val = *(const v4i*)(Kh + (size_t)r * D + 16 * c16);
+        *(v4i*)(sK + r * KROW + 16 * c16) = val;
+    }
+    for (int sb = tid; sb < (npad / 4) * (D / 16); sb += nthr) {
+        const int tq = sb % (D / 16), r0 = 4 * (sb / (D / 16));
+        stage_v_4x16(Vh, D, N, r0, tq, sV, VROW, r0 & ~31, r0 & 31);
+    }
+    v4i qreg[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) {
+        qreg[s] = v4i{0, 0, 0, 0};
+        if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
+    }
+    __syncthreads();
+    if (row0 >= N) return;            // wavefront without query rows (after the only barrier)
+
+    const int32_t* bias_row = nullptr;
+    if (BIAS) {
+        const int b = bh / a.H, h = bh % a.H;
+        bias_row = a.bias + ((size_t)(b % a.bias_B) * a.bias_H + (size_t)(h % a.bias_H)) * N * N +
+                   (size_t)(i < N ? i : 0) * N;
+    }
+    const ExpConst c = make_exp_const(a);
+    RowState<D> st;
+#pragma unroll
+    for (int t = 0; t < D / 32; ++t) st.acc[t] = v16i{0};
+    st.l = 0;
+    st.m = kMInit;
+
+    const int Tc = (N + BC - 1) / BC;
+    for (int j = 0; j < Tc; ++j) {
+        const int c0 = j * BC;
+        const int n_valid = min(BC, N - c0);
+        process_tile<D, BC, BIAS, NARROW>(st, qreg, sK + (size_t)c0 * KROW, KROW, sV + c0, VROW, n_valid, j == 0,
+                                          BIAS ? bias_row + c0 : nullptr, c, a.a_mul, li, g);
+    }
+    if (i >= N) return;
+    int8_t* Orow = a.O + head_off + (size_t)i * D;
+    if (NARROW && !a.out_round) normalise_store<D, 15>(st, Orow, g, false);
+    else normalise_store<D, 20>(st, Orow, g, a.out_round != 0);
+}
+
+// -------------------------------------------------------------------------- stream kernel
+
+constexpr int kStreamWaves = 4;
+constexpr int kStreamThreads = kStreamWaves * 64;
+constexpr int kStreamRows = kStreamWaves * 32;
+
+template <int D, int BC, bool BIAS, bool NARROW>
+__global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const QflashKernelArgs a) {
+    constexpr int KSTEPS = D / 32;
+    constexpr int KROW = D + 16;
+    constexpr int VROW = BC + 16;
     __shared__ __align__(16) int8_t sK[BC * KROW];
     __shared__ __align__(16) int8_t sV[D * VROW];
 
-    // XCD-aware placement: workgroup ids are dealt round-robin to the 8 XCDs, so XCD x gets the
-    // ids congruent to x; give it a contiguous range of units so that the query tiles of one head
-    // meet in one L2.
     const int wg = blockIdx.x;
     const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
     if (unit >= a.n_units) return;
@@ -92,12 +406,10 @@ __global__ __launch_bounds__(kThreads) void qflash_fwd_kernel(const QflashKernel
     const int N = a.N;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int g = lane >> 5;          // which half of the k-slots / result rows this lane holds
-    const int li = lane & 31;
-    const int row0 = qt * kRowsPerWg + wave * kRowsPerWave;
-    const int i = row0 + li;          // query row of this lane
+    const int lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, li = lane & 31;
+    const int row0 = qt * kStreamRows + wave * 32;
+    const int i = row0 + li;
     const bool wave_active = row0 < N;
 
     const size_t head_off = (size_t)bh * N * D;
@@ -110,186 +422,110 @@ __global__ __launch_bounds__(kThreads) void qflash_fwd_kernel(const QflashKernel
         bias_row = a.bias + ((size_t)(b % a.bias_B) * a.bias_H + (size_t)(h % a.bias_H)) * N * N +
                    (size_t)(i < N ? i : 0) * N;
     }
-
-    // Q rows of this lane as MFMA B operand: 16 contiguous bytes per 32-wide step.
     v4i qreg[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
         qreg[s] = v4i{0, 0, 0, 0};
         if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
     }
-
-    v16i acc[TB];
+    const ExpConst c = make_exp_const(a);
+    RowState<D> st;
 #pragma unroll
-    for (int t = 0; t < TB; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][v] = 0;
-    int l = 0;
-    int m = kMInit;
+    for (int t = 0; t < D / 32; ++t) st.acc[t] = v16i{0};
+    st.l = 0;
+    st.m = kMInit;
 
     const int Tc = (N + BC - 1) / BC;
     for (int j = 0; j < Tc; ++j) {
         const int c0 = j * BC;
         if (j > 0) __syncthreads();   // everyone is done reading the previous tile
-
-        // ---- K tile -> LDS, row-major, 16-byte chunks (coalesced: consecutive threads read
-        //      consecutive chunks of consecutive rows)
-        constexpr int KCH = BC * D / 16;
-#pragma unroll
-        for (int ch = tid; ch < KCH; ch += kThreads) {
+        for (int ch = tid; ch < BC * (D / 16); ch += kStreamThreads) {
             const int r = ch / (D / 16), c16 = ch % (D / 16);
             v4i val = {0, 0, 0, 0};
             if (c0 + r < N) val = *(const v4i*)(Kh + (size_t)(c0 + r) * D + 16 * c16);
             *(v4i*)(sK + r * KROW + 16 * c16) = val;
         }
-        // ---- V tile -> LDS, transposed to [t][kv], kv columns permuted to the result-layout
-        //      order of the first product.  Each thread transposes 4 kv rows x 4 features.
-        constexpr int VSB = (BC / 4) * (D / 4);
-#pragma unroll
-        for (int sb = tid; sb < VSB; sb += kThreads) {
-            const int tg = sb % (D / 4), cg = sb / (D / 4);
-            unsigned rw[4];
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int c = c0 + 4 * cg + b;
-                rw[b] = 0;
-                if (c < N) rw[b] = *(const unsigned*)(Vh + (size_t)c * D + 4 * tg);
-            }
-            // kv row (within the tile) 4*cg = 32*kb + 8*a4 + 4*g2  ->  slot 32*kb + 16*g2 + 4*a4
-            const int w = (4 * cg) & 31;
-            const int pos = ((4 * cg) & ~31) + 16 * ((w >> 2) & 1) + 4 * (w >> 3);
-#pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                const unsigned o = ((rw[0] >> (8 * f)) & 0xffu) | (((rw[1] >> (8 * f)) & 0xffu) << 8) |
-                                   (((rw[2] >> (8 * f)) & 0xffu) << 16) | (((rw[3] >> (8 * f)) & 0xffu) << 24);
-                *(unsigned*)(sV + (4 * tg + f) * VROW + pos) = o;
-            }
+        for (int sb = tid; sb < (BC / 4) * (D / 16); sb += kStreamThreads) {
+            const int tq = sb % (D / 16), r0 = 4 * (sb / (D / 16));
+            stage_v_4x16(Vh, D, N, c0 + r0, tq, sV, VROW, r0 & ~31, r0 & 31);
         }
         __syncthreads();
         if (!wave_active) continue;   // uniform per wavefront; still takes part in the barriers
-
-        // ---- step 1: S^T blocks (32 kv rows x 32 queries each)
-        v16i s[KB];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[kb][v] = 0;
-            if (c0 + 32 * kb < N) {
-#pragma unroll
-                for (int st = 0; st < KSTEPS; ++st) {
-                    const v4i ka = *(const v4i*)(sK + (32 * kb + li) * KROW + 32 * st + 16 * g);
-                    s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka, qreg[st], s[kb], 0, 0, 0);
-                }
-            }
-        }
-        // ---- bias, exclusion and the ragged end of the sequence
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const bool ragged = c0 + 32 * kb + 32 > N;
-            if (BIAS || ragged) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int c = c0 + 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
-                    int val = s[kb][v];
-                    bool excl = c >= N;
-                    if (BIAS && !excl) {
-                        const int bv = bias_row[c];
-                        excl = (bv == INT32_MIN);
-                        val += excl ? 0 : bv;
-                    }
-                    s[kb][v] = excl ? kNegBig : val;
-                }
-            }
-        }
-        // ---- steps 2,3: row maximum over the tile, running maximum
-        int m_new = m;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-            if (c0 + 32 * kb < N) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) m_new = max(m_new, s[kb][v]);
-            }
-        m_new = max(m_new, xor32(m_new));
-        // ---- step 4: max-offset factor alpha, brought to 16 fractional bits
-        const int a_hat = shift_exp2(max(m - m_new, a.x_floor), a);
-        const int alpha16 = min((int)(((unsigned)a_hat * (unsigned)a.a_mul) >> 14), 65536);
-        // ---- steps 5,6,7: score intensity, requantisation to int8, row sum
-        v4i pk[KB];
-        int rowsum = 0;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            pk[kb] = v4i{0, 0, 0, 0};
-            if (c0 + 32 * kb < N) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int x = max(s[kb][v] - m_new, a.x_floor);
-                    const int pv = requant(shift_exp2(x, a), a);
-                    rowsum += pv;
-                    pk[kb][v >> 2] |= pv << (8 * (v & 3));
-                }
-            }
-        }
-        rowsum += xor32(rowsum);
-        // ---- steps 9,10: ScaleRelease of the running denominator and numerator
-        l = scale_release(l, alpha16) + rowsum;
-        if (j > 0) {
-#pragma unroll
-            for (int t = 0; t < TB; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[t][v] = scale_release(acc[t][v], alpha16);
-        }
-        // ---- step 8: O^T += V_j^T P^T
-#pragma unroll
-        for (int t = 0; t < TB; ++t)
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-                if (c0 + 32 * kb < N) {
-                    const v4i va = *(const v4i*)(sV + (32 * t + li) * VROW + 32 * kb + 16 * g);
-                    acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], acc[t], 0, 0, 0);
-                }
-        m = m_new;
+        const int n_valid = min(BC, N - c0);
+        process_tile<D, BC, BIAS, NARROW>(st, qreg, sK, KROW, sV, VROW, n_valid, j == 0,
+                                          BIAS ? bias_row + c0 : nullptr, c, a.a_mul, li, g);
     }
-
-    // ---- step 11: integer normalisation, saturate to int8, store.  Lane holds features
-    //      32*t + 8*(v/4) + 4*g + v%4 of query i: four consecutive features per dword.
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
-#pragma unroll
-    for (int t = 0; t < TB; ++t)
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            unsigned word = 0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int o = acc[t][4 * v4 + b];
-                int q = 0;
-                if (l != 0) q = a.out_round ? floor_div_pos(2 * o + l, 2 * l) : floor_div_pos(o, l);
-                q = min(127, max(-128, q));
-                word |= ((unsigned)q & 0xffu) << (8 * b);
-            }
-            *(unsigned*)(Orow + 32 * t + 8 * v4 + 4 * g) = word;
+    if (NARROW && !a.out_round) normalise_store<D, 15>(st, Orow, g, false);
+    else normalise_store<D, 20>(st, Orow, g, a.out_round != 0);
+}
+
+// ------------------------------------------------------------------------------ launchers
+
+template <int D, int BC, bool BIAS, bool NARROW>
+int launch_one(const QflashKernelArgs& a, bool resident, size_t lds_bytes, int lds_limit, int threads,
+               hipStream_t stream) {
+    const dim3 grid((unsigned)(8 * a.units_per_xcd));
+    if (resident) {
+        auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW>;
+        static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
+        if (!attr_set) {
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit) !=
+                hipSuccess)
+                return (int)hipGetLastError();
+            attr_set = true;
         }
+        hipLaunchKernelGGL(kern, grid, dim3((unsigned)threads), lds_bytes, stream, a);
+    } else {
+        hipLaunchKernelGGL((qflash_fwd_stream<D, BC, BIAS, NARROW>), grid, dim3(kStreamThreads), 0, stream, a);
+    }
+    return (int)hipGetLastError();
 }
 
 template <int D, int BC>
-int launch(const QflashKernelArgs& a, hipStream_t stream) {
-    const dim3 grid((unsigned)(8 * a.units_per_xcd)), block(kThreads);
-    if (a.bias)
-        hipLaunchKernelGGL((qflash_fwd_kernel<D, BC, true>), grid, block, 0, stream, a);
-    else
-        hipLaunchKernelGGL((qflash_fwd_kernel<D, BC, false>), grid, block, 0, stream, a);
-    return (int)hipGetLastError();
+int launch_dbc(const QflashKernelArgs& a, bool resident, size_t lds, int lds_limit, int threads, hipStream_t st) {
+    const bool narrow = a.N <= 256;
+    if (a.bias) {
+        return narrow ? launch_one<D, BC, true, true>(a, resident, lds, lds_limit, threads, st)
+                      : launch_one<D, BC, true, false>(a, resident, lds, lds_limit, threads, st);
+    }
+    return narrow ? launch_one<D, BC, false, true>(a, resident, lds, lds_limit, threads, st)
+                  : launch_one<D, BC, false, false>(a, resident, lds, lds_limit, threads, st);
 }
 
 }  // namespace
 
-int qflash_fwd_rows_per_workgroup(int, int) { return kRowsPerWg; }
+// LDS bytes of the resident kernel for a head of N rows, or 0 if it does not fit.
+static size_t resident_lds_bytes(int N, int d, int lds_limit) {
+    const size_t npad = (size_t)((N + 31) & ~31);
+    const size_t bytes = npad * (size_t)(d + 16) + (size_t)d * (npad + 16);
+    return bytes <= (size_t)lds_limit ? bytes : 0;
+}
 
-int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, void* stream) {
+int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* a) {
+    (void)kv_tile;
+    const size_t lds = resident_lds_bytes(N, d, lds_limit);
+    if (lds != 0) {
+        const int nblk = (N + 31) / 32;
+        const int tiles = (nblk + 15) / 16;                 // at most 16 wavefronts per workgroup
+        const int waves = (nblk + tiles - 1) / tiles;       // balanced
+        a->rows_per_wg = 32 * waves;
+    } else {
+        a->rows_per_wg = kStreamRows;
+    }
+    a->n_qtiles = (N + a->rows_per_wg - 1) / a->rows_per_wg;
+    return 0;
+}
+
+int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    if (d == 64 && kv_tile == 64) return launch<64, 64>(a, st);
-    if (d == 64 && kv_tile == 128) return launch<64, 128>(a, st);
-    if (d == 32 && kv_tile == 64) return launch<32, 64>(a, st);
-    if (d == 32 && kv_tile == 128) return launch<32, 128>(a, st);
+    const size_t lds = resident_lds_bytes(a.N, d, lds_limit);
+    const bool resident = lds != 0;
+    const int threads = resident ? 2 * a.rows_per_wg : kStreamThreads;
+    if (d == 64 && kv_tile == 64) return launch_dbc<64, 64>(a, resident, lds, lds_limit, threads, st);
+    if (d == 64 && kv_tile == 128) return launch_dbc<64, 128>(a, resident, lds, lds_limit, threads, st);
+    if (d == 32 && kv_tile == 64) return launch_dbc<32, 64>(a, resident, lds, lds_limit, threads, st);
+    if (d == 32 && kv_tile == 128) return launch_dbc<32, 128>(a, resident, lds, lds_limit, threads, st);
     return (int)hipErrorInvalidValue;
 }
