@@ -80,7 +80,8 @@ struct ExpConst {
 // compose, so y = (r + 2 s_inv) >> (q + 1).  In the clamped range x' fits 24 bits, 0 <= q <= 28
 // and r + 2 s_inv is positive, so the logical shift is exact.
 __device__ __forceinline__ int shift_exp2(int t, int neg_m, const ExpConst& c) {
-    const int xs = (t + neg_m) << c.k;
+    int xs;   // (t + neg_m) << k in one operation
+    asm("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(xs) : "v"(t), "v"(neg_m), "s"(c.k));
     const int q = mulhi24(xs, c.M);
     const int r2 = __mul24(q, c.s_inv) + xs + c.two_s_inv;
     return (int)((unsigned)r2 >> (q + 1));
@@ -124,12 +125,15 @@ struct RowState {
 
 // One KV tile for one wavefront.  sK: K rows of the tile (row pitch KROW), sV: V^T with the tile's
 // columns starting at column 0 (row pitch VROW).  n_valid = number of real kv rows in the tile.
-template <int D, int BC, bool BIAS, bool NARROW>
+template <int D, int BC, bool BIAS, bool NARROW, bool FULL, bool FIRST>
 __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
-                                            const int8_t* sV, int VROW, int n_valid, bool first,
+                                            const int8_t* sV, int VROW, int n_valid_rt,
                                             const int32_t* bias_row /* + c0 */, const ExpConst& c,
                                             int a_mul, int li, int g) {
     constexpr int KSTEPS = D / 32, TB = D / 32, KB = BC / 32;
+    // FULL: the tile has all BC kv rows, every "is this group inside the sequence" test below is
+    // true at compile time and the tile is one straight line of code.
+    const int n_valid = FULL ? BC : n_valid_rt;
     // ---- step 1: S^T blocks (32 kv rows x 32 queries each)
     v16i s[KB];
 #pragma unroll
@@ -182,7 +186,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
     const int lo = m_new + c.x_floor;
     // ---- step 4: max-offset factor alpha, brought to 16 fractional bits
     int alpha16 = 0;
-    if (!first) {
+    if (!FIRST) {
         const int a_hat = shift_exp2(max(st.m, lo), neg_m, c);
         alpha16 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536);
     }
@@ -218,7 +222,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
     }
     rowsum += other_half(rowsum);
     // ---- steps 9,10: ScaleRelease of the running denominator and numerator
-    if (first) {
+    if (FIRST) {
         st.l = rowsum;
     } else {
         st.l = scale_release<NARROW>(st.l, alpha16) + rowsum;
@@ -261,17 +265,19 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
     for (int t = 0; t < TB; ++t)
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4) {
-            unsigned word = 0;
+            unsigned hi[4];
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int o = st.acc[t][4 * a4 + b];
                 int u = (o * num_mul + bias_u) << z;
                 u = min(max(u, 0), u_max);
-                unsigned tq;
-                if (L <= 15) tq = umulhi24((unsigned)u, R) >> (2 * L + 8 - 32);
-                else tq = __umulhi((unsigned)u, R) >> (2 * L + 8 - 32);
-                word |= tq << (8 * b);
+                hi[b] = (L <= 15) ? umulhi24((unsigned)u, R) : __umulhi((unsigned)u, R);
             }
+            constexpr unsigned sh = 2 * L + 8 - 32;     // quotient = hi >> sh, in [0, 255]
+            unsigned word = shr_into_byte<0>(0u, sh, hi[0]);
+            word = shr_into_byte<1>(word, sh, hi[1]);
+            word = shr_into_byte<2>(word, sh, hi[2]);
+            word = shr_into_byte<3>(word, sh, hi[3]);
             word ^= 0x80808080u;
             if (empty) word = 0;
             *(unsigned*)(Orow + 32 * t + 8 * a4 + 4 * g) = word;
@@ -285,34 +291,54 @@ __device__ __forceinline__ ExpConst make_exp_const(const QflashKernelArgs& a) {
     return c;
 }
 
-// V rows [r0, r0+4) x features [16*tq, 16*tq+16) -> V^T in LDS, kv columns in result-layout order.
-// col_base = LDS column of kv row r0's 32-row block start; r_in_blk = r0 % 32 (multiple of 4).
-__device__ __forceinline__ void stage_v_4x16(const int8_t* Vh, int D, int N, int r0, int tq, int8_t* sV, int VROW,
-                                             int lds_col_blk, int r_in_blk) {
-    v4i rw[4];
+// 4x4 byte transpose: rows r[0..3] (byte f = feature f) -> o[f] = (r0.f, r1.f, r2.f, r3.f).
+// v_perm_b32 picks result bytes from the 8 bytes {first operand (4..7), second operand (0..3)}.
+__device__ __forceinline__ void transpose4x4(const unsigned r[4], unsigned o[4]) {
+    const unsigned t0 = __builtin_amdgcn_perm(r[1], r[0], 0x05010400u);
+    const unsigned t1 = __builtin_amdgcn_perm(r[1], r[0], 0x07030602u);
+    const unsigned t2 = __builtin_amdgcn_perm(r[3], r[2], 0x05010400u);
+    const unsigned t3 = __builtin_amdgcn_perm(r[3], r[2], 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+}
+
+// V rows [r0, r0+4) x features [8*t8, 8*t8+8) -> V^T in LDS, kv columns in result-layout order.
+// lds_col_blk = LDS column where the 32-row kv block of r0 starts; r_in_blk = r0 % 32 (multiple of 4).
+typedef int v2i __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void stage_v_4x8(const int8_t* Vh, int D, int N, int r0, int t8, int8_t* sV, int VROW,
+                                            int lds_col_blk, int r_in_blk) {
+    v2i rw[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-        rw[b] = v4i{0, 0, 0, 0};
-        if (r0 + b < N) rw[b] = *(const v4i*)(Vh + (size_t)(r0 + b) * D + 16 * tq);
+        rw[b] = v2i{0, 0};
+        if (r0 + b < N) rw[b] = *(const v2i*)(Vh + (size_t)(r0 + b) * D + 8 * t8);
     }
     // kv row 8*a4 + 4*g2 + b of a block  ->  slot 16*g2 + 4*a4 + b
     const int pos = lds_col_blk + 16 * ((r_in_blk >> 2) & 1) + 4 * (r_in_blk >> 3);
 #pragma unroll
-    for (int w = 0; w < 4; ++w)
+    for (int w = 0; w < 2; ++w) {
+        const unsigned r[4] = {(unsigned)rw[0][w], (unsigned)rw[1][w], (unsigned)rw[2][w], (unsigned)rw[3][w]};
+        unsigned o[4];
+        transpose4x4(r, o);
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            const unsigned o = (((unsigned)rw[0][w] >> (8 * f)) & 0xffu) | ((((unsigned)rw[1][w] >> (8 * f)) & 0xffu) << 8) |
-                               ((((unsigned)rw[2][w] >> (8 * f)) & 0xffu) << 16) | ((((unsigned)rw[3][w] >> (8 * f)) & 0xffu) << 24);
-            *(unsigned*)(sV + (16 * tq + 4 * w + f) * VROW + pos) = o;
-        }
+        for (int f = 0; f < 4; ++f) *(unsigned*)(sV + (8 * t8 + 4 * w + f) * VROW + pos) = o[f];
+    }
 }
 
 // ------------------------------------------------------------------------ resident kernel
 
 extern __shared__ __align__(16) int8_t smem[];
 
+// Wavefronts per workgroup.  Short sequences (N <= 256) need at most 8; the kernel is then held to
+// 128 registers so that two workgroups share a CU.  Longer sequences get up to 12 wavefronts of
+// up to 168 registers (the 32-bit rescale and wider tiles need more live values).
+template <bool NARROW>
+constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
+
 template <int D, int BC, bool BIAS, bool NARROW>
-__global__ __launch_bounds__(1024) void qflash_fwd_resident(const QflashKernelArgs a) {
+__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
     const int N = a.N;
@@ -345,9 +371,9 @@ __global__ __launch_bounds__(1024) void qflash_fwd_resident(const QflashKernelAr
         if (r < N) val = *(const v4i*)(Kh + (size_t)r * D + 16 * c16);
         *(v4i*)(sK + r * KROW + 16 * c16) = val;
     }
-    for (int sb = tid; sb < (npad / 4) * (D / 16); sb += nthr) {
-        const int tq = sb % (D / 16), r0 = 4 * (sb / (D / 16));
-        stage_v_4x16(Vh, D, N, r0, tq, sV, VROW, r0 & ~31, r0 & 31);
+    for (int sb = tid; sb < (npad / 4) * (D / 8); sb += nthr) {
+        const int t8 = sb % (D / 8), r0 = 4 * (sb / (D / 8));
+        stage_v_4x8(Vh, D, N, r0, t8, sV, VROW, r0 & ~31, r0 & 31);
     }
     v4i qreg[KSTEPS];
 #pragma unroll
@@ -371,13 +397,21 @@ __global__ __launch_bounds__(1024) void qflash_fwd_resident(const QflashKernelAr
     st.l = 0;
     st.m = kMInit;
 
-    const int Tc = (N + BC - 1) / BC;
-    for (int j = 0; j < Tc; ++j) {
-        const int c0 = j * BC;
-        const int n_valid = min(BC, N - c0);
-        process_tile<D, BC, BIAS, NARROW>(st, qreg, sK + (size_t)c0 * KROW, KROW, sV + c0, VROW, n_valid, j == 0,
-                                          BIAS ? bias_row + c0 : nullptr, c, a.a_mul, li, g);
+    // First tile (no rescale), the remaining full tiles as one straight-line loop body, then the
+    // ragged tile if the sequence does not end on a tile boundary.
+    const int n_full = N / BC, rem = N - n_full * BC;
+#define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
+    process_tile<D, BC, BIAS, NARROW, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,          \
+                                                     sV + (J_) * BC, VROW, NV_,                              \
+                                                     BIAS ? bias_row + (J_) * BC : nullptr, c, a.a_mul, li, g)
+    if (n_full > 0) {
+        QF_TILE(true, true, 0, BC);
+        for (int j = 1; j < n_full; ++j) QF_TILE(true, false, j, BC);
+        if (rem > 0) QF_TILE(false, false, n_full, rem);
+    } else {
+        QF_TILE(false, true, 0, rem);
     }
+#undef QF_TILE
     if (i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
     if (NARROW && !a.out_round) normalise_store<D, 15>(st, Orow, g, false);
@@ -445,15 +479,20 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
             if (c0 + r < N) val = *(const v4i*)(Kh + (size_t)(c0 + r) * D + 16 * c16);
             *(v4i*)(sK + r * KROW + 16 * c16) = val;
         }
-        for (int sb = tid; sb < (BC / 4) * (D / 16); sb += kStreamThreads) {
-            const int tq = sb % (D / 16), r0 = 4 * (sb / (D / 16));
-            stage_v_4x16(Vh, D, N, c0 + r0, tq, sV, VROW, r0 & ~31, r0 & 31);
+        for (int sb = tid; sb < (BC / 4) * (D / 8); sb += kStreamThreads) {
+            const int t8 = sb % (D / 8), r0 = 4 * (sb / (D / 8));
+            stage_v_4x8(Vh, D, N, c0 + r0, t8, sV, VROW, r0 & ~31, r0 & 31);
         }
         __syncthreads();
         if (!wave_active) continue;   // uniform per wavefront; still takes part in the barriers
         const int n_valid = min(BC, N - c0);
-        process_tile<D, BC, BIAS, NARROW>(st, qreg, sK, KROW, sV, VROW, n_valid, j == 0,
-                                          BIAS ? bias_row + c0 : nullptr, c, a.a_mul, li, g);
+        const int32_t* brow = BIAS ? bias_row + c0 : nullptr;
+        if (j == 0)
+            process_tile<D, BC, BIAS, NARROW, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
+        else if (n_valid == BC)
+            process_tile<D, BC, BIAS, NARROW, true, false>(st, qreg, sK, KROW, sV, VROW, BC, brow, c, a.a_mul, li, g);
+        else
+            process_tile<D, BC, BIAS, NARROW, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
     }
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
@@ -504,11 +543,11 @@ static size_t resident_lds_bytes(int N, int d, int lds_limit) {
 }
 
 int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* a) {
-    (void)kv_tile;
     const size_t lds = resident_lds_bytes(N, d, lds_limit);
     if (lds != 0) {
         const int nblk = (N + 31) / 32;
-        const int tiles = (nblk + 15) / 16;                 // at most 16 wavefronts per workgroup
+        const int max_waves = N <= 256 ? resident_max_waves<true>() : resident_max_waves<false>();
+        const int tiles = (nblk + max_waves - 1) / max_waves;
         const int waves = (nblk + tiles - 1) / tiles;       // balanced
         a->rows_per_wg = 32 * waves;
     } else {
