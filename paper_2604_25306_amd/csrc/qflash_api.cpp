@@ -42,7 +42,8 @@ bool params_ok(const qflash_params& p) {
     // M * s_inv must be -2^32 to within 0.1 %: both come from the same real scale.
     const int64_t prod = (int64_t)p.exp_mul * (int64_t)p.s_inv + ((int64_t)1 << 32);
     if (prod > ((int64_t)1 << 32) / 1000 || prod < -(((int64_t)1 << 32) / 1000)) return false;
-    if (p.p_shift < 1 || p.p_shift > 30 || p.p_mul < 1 || p.p_mul >= (1 << 12)) return false;
+    // the kernel multiplies by p_mul << (24 - p_shift), a 24-bit operand, so that P lands in byte 3
+    if (p.p_shift < 8 || p.p_shift > 24 || p.p_mul < 1 || ((int64_t)p.p_mul << (24 - p.p_shift)) >= (1 << 23)) return false;
     // 1.0 (= s_inv) must requantise to at most 127 so that P fits a signed byte.
     if ((int64_t)p.s_inv * p.p_mul >= ((int64_t)128 << p.p_shift)) return false;
     if (p.a_mul < 1 || (int64_t)p.s_inv * p.a_mul >= ((int64_t)1 << 31)) return false;

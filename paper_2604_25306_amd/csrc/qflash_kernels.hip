@@ -44,10 +44,6 @@ __device__ __forceinline__ int mulhi24(int a, int b) {
     const int a24 = (a << 8) >> 8, b24 = (b << 8) >> 8;
     return (int)(((long long)a24 * (long long)b24) >> 32);
 }
-// (a * b) >> 32 for operands below 2^24: v_mul_hi_u32_u24.
-__device__ __forceinline__ unsigned umulhi24(unsigned a, unsigned b) {
-    return (unsigned)(((unsigned long long)(a & 0xffffffu) * (unsigned long long)(b & 0xffffffu)) >> 32);
-}
 // packed.byte[B] = (v >> sh) & 0xff, other bytes kept: the shift and the byte insert are one
 // SDWA instruction.  The caller guarantees (v >> sh) < 256.
 template <int B>
@@ -70,33 +66,66 @@ __device__ __forceinline__ int other_half(int v) { return __shfl_xor(v, 32, 64);
 
 // Loop-invariant constants of Algorithm 2 / Eq. 10 kept in registers.
 struct ExpConst {
-    int k, s_inv, two_s_inv, M, p_mul, x_floor;
-    unsigned p_shift;
+    int k, s_inv, x_floor;   // uniform (scalar registers)
+    int M_v;                 // exp_mul, in a vector register
+    int two_s_inv_v;         // 2 * s_inv, in a vector register
+    int p_mul_hi_v;          // p_mul << (24 - p_shift): the requantised weight lands in byte 3
 };
 
-// Algorithm 2 for a score t already clamped from below to (m + x_floor); neg_m = -m.
+// Copy a uniform value into a vector register and keep it there: on this chip a two-operand
+// multiply / max / shift with a scalar source issues slower than with two vector sources.
+__device__ __forceinline__ int to_vgpr(int v) {
+    int r;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "s"(v));
+    return r;
+}
+
+// Algorithm 2 for a score t already clamped from below to (m + x_floor).
 //   x' = (t - m) << k,  q = (x' * M) >> 32,  r = x' + q * s_inv,  y = ((r >> 1) + s_inv) >> q.
 // (r >> 1) + s_inv = floor((r + 2 s_inv) / 2) and nested floors of divisions by powers of two
 // compose, so y = (r + 2 s_inv) >> (q + 1).  In the clamped range x' fits 24 bits, 0 <= q <= 28
 // and r + 2 s_inv is positive, so the logical shift is exact.
-__device__ __forceinline__ int shift_exp2(int t, int neg_m, const ExpConst& c) {
-    int xs;   // (t + neg_m) << k in one operation
-    asm("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(xs) : "v"(t), "v"(neg_m), "s"(c.k));
-    const int q = mulhi24(xs, c.M);
-    const int r2 = __mul24(q, c.s_inv) + xs + c.two_s_inv;
+// KZ (k == 0): x' = t - m and x' + 2 s_inv = t - (m - 2 s_inv) are two cheap subtractions.
+template <bool KZ>
+__device__ __forceinline__ int shift_exp2(int t, int m, int m2 /* m - 2 s_inv */, const ExpConst& c) {
+    int xs, xs2;
+    if (KZ) {
+        xs = t - m;
+        xs2 = t - m2;
+    } else {
+        const int neg_m = -m;
+        asm("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(xs) : "v"(t), "v"(neg_m), "s"(c.k));
+        xs2 = xs + c.two_s_inv_v;
+    }
+    const int q = mulhi24(xs, c.M_v);
+    const int r2 = __mul24(q, c.s_inv) + xs2;
     return (int)((unsigned)r2 >> (q + 1));
 }
 
-// ScaleRelease with alpha in 16 fractional bits: floor(x * alpha16 / 2^16).
-// NARROW: |x| < 2^23, three full-rate operations.  Otherwise |x| < 2^26: (x*2^5 * a*2^11) >> 32.
-template <bool NARROW>
-__device__ __forceinline__ int scale_release(int x, int alpha16) {
-    if (NARROW) {
-        const int hi = mulhi24(x, alpha16);
-        const unsigned lo = (unsigned)__mul24(x, alpha16);
-        return (int)__builtin_amdgcn_alignbit((unsigned)hi, lo, 16);
-    }
-    return __mulhi(x << 5, alpha16 << 11);
+// Gather byte 3 of four dwords into one dword (v_perm_b32: selector bytes 0-3 pick from the
+// second operand, 4-7 from the first).
+__device__ __forceinline__ unsigned pack_byte3(unsigned p0, unsigned p1, unsigned p2, unsigned p3) {
+    unsigned w = __builtin_amdgcn_perm(p1, p0, 0x07030703u);   // [p0.3, p1.3, .., ..]
+    w = __builtin_amdgcn_perm(p2, w, 0x07070100u);             // [p0.3, p1.3, p2.3, ..]
+    return __builtin_amdgcn_perm(p3, w, 0x07020100u);          // [p0.3, p1.3, p2.3, p3.3]
+}
+template <int BYTE>
+__device__ __forceinline__ unsigned pack_byte(unsigned p0, unsigned p1, unsigned p2, unsigned p3) {
+    constexpr unsigned b = BYTE, h = BYTE + 4;
+    unsigned w = __builtin_amdgcn_perm(p1, p0, (h << 24) | (b << 16) | (h << 8) | b);
+    w = __builtin_amdgcn_perm(p2, w, (h << 24) | (h << 16) | 0x0100u);
+    return __builtin_amdgcn_perm(p3, w, (h << 24) | 0x020100u);
+}
+
+// ScaleRelease with alpha in 16 fractional bits: floor(x * alpha16 / 2^16) = ((x << 2) * (alpha16 << 14)) >> 32.
+// |x| < 2^26 and alpha16 <= 2^16 keep both factors inside 32 signed bits; the 32-bit multiply-high is
+// a full-rate instruction on gfx950.  alpha14 = alpha16 << 14 is formed once per row and tile.
+// The shift names alpha14 as an (unused) input so that it cannot be scheduled before alpha is known:
+// hoisted to the top of the tile it would keep a second copy of every accumulator alive.
+__device__ __forceinline__ int scale_release(int x, int alpha14) {
+    int x4;
+    asm("v_lshlrev_b32 %0, 2, %1 ; after %2" : "=v"(x4) : "v"(x), "v"(alpha14));
+    return __mulhi(x4, alpha14);
 }
 
 // ceil(2^(2L+8) / d) for d in (2^(L-1), 2^L] by restoring division: integer only, L+9 steps.
@@ -125,7 +154,7 @@ struct RowState {
 
 // One KV tile for one wavefront.  sK: K rows of the tile (row pitch KROW), sV: V^T with the tile's
 // columns starting at column 0 (row pitch VROW).  n_valid = number of real kv rows in the tile.
-template <int D, int BC, bool BIAS, bool NARROW, bool FULL, bool FIRST>
+template <int D, int BC, bool BIAS, bool KZ, bool FULL, bool FIRST>
 __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
                                             const int8_t* sV, int VROW, int n_valid_rt,
                                             const int32_t* bias_row /* + c0 */, const ExpConst& c,
@@ -182,13 +211,13 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                 m_new = max(m_new, max(s[kb][4 * a4 + 2], s[kb][4 * a4 + 3]));
             }
     m_new = max(m_new, other_half(m_new));
-    const int neg_m = -m_new;
     const int lo = m_new + c.x_floor;
-    // ---- step 4: max-offset factor alpha, brought to 16 fractional bits
-    int alpha16 = 0;
+    const int m2 = m_new - 2 * c.s_inv;
+    // ---- step 4: max-offset factor alpha, brought to 16 fractional bits (kept as alpha16 << 14)
+    int alpha14 = 0;
     if (!FIRST) {
-        const int a_hat = shift_exp2(max(st.m, lo), neg_m, c);
-        alpha16 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536);
+        const int a_hat = shift_exp2<KZ>(max(st.m, lo), m_new, m2, c);
+        alpha14 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536) << 14;
     }
     // ---- steps 5,6,7: score intensity, requantisation to int8 (Eq. 10), row sum
     v4i pk[KB];
@@ -199,38 +228,32 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4)
             if (32 * kb + 8 * a4 < n_valid) {
-                unsigned w = 0;
-                {
-                    const int y = shift_exp2(max(s[kb][4 * a4 + 0], lo), neg_m, c);
-                    w = shr_into_byte<0>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
+                unsigned pr[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int y = shift_exp2<KZ>(max(s[kb][4 * a4 + b], lo), m_new, m2, c);
+                    pr[b] = (unsigned)__mul24(y, c.p_mul_hi_v);       // Eq. 10, result in byte 3
                 }
-                {
-                    const int y = shift_exp2(max(s[kb][4 * a4 + 1], lo), neg_m, c);
-                    w = shr_into_byte<1>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
-                }
-                {
-                    const int y = shift_exp2(max(s[kb][4 * a4 + 2], lo), neg_m, c);
-                    w = shr_into_byte<2>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
-                }
-                {
-                    const int y = shift_exp2(max(s[kb][4 * a4 + 3], lo), neg_m, c);
-                    w = shr_into_byte<3>(w, c.p_shift, (unsigned)__mul24(y, c.p_mul));
-                }
+                const unsigned w = pack_byte3(pr[0], pr[1], pr[2], pr[3]);
                 pk[kb][a4] = (int)w;
                 rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
             }
     }
     rowsum += other_half(rowsum);
+    // Keep the phases apart: letting the scheduler overlap the rescale below with the element-wise
+    // work above only lengthens live ranges (spills) without gaining issue slots.
+    __builtin_amdgcn_sched_barrier(0);
     // ---- steps 9,10: ScaleRelease of the running denominator and numerator
     if (FIRST) {
         st.l = rowsum;
     } else {
-        st.l = scale_release<NARROW>(st.l, alpha16) + rowsum;
+        st.l = scale_release(st.l, alpha14) + rowsum;
 #pragma unroll
         for (int t = 0; t < TB; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release<NARROW>(st.acc[t][v], alpha16);
+            for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14);
     }
+    __builtin_amdgcn_sched_barrier(0);
     // ---- step 8: O^T += V_j^T P^T
 #pragma unroll
     for (int t = 0; t < TB; ++t)
@@ -247,20 +270,22 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 // per element.  With u = O + 128 l clamped to [0, 256 l), t = floor(u / l) lies in [0, 255] and
 // floor(O / l) saturated to [-128, 127] equals t - 128, i.e. byte t ^ 0x80.  l is normalised to
 // l' = l << z in (2^(L-1), 2^L] and R = ceil(2^(2L+8) / l'); then floor(u' R / 2^(2L+8)) is exact
-// for every u' < 256 l' because u' (R l' - 2^(2L+8)) < 2^(L+8) 2^L.
+// for every u' < 256 l' because u' (R l' - 2^(2L+8)) < 2^(L+8) 2^L.  L = 16 or 20 puts the quotient
+// into byte 1 or 2 of the high product word.  Nearest: floor((2 O + l) / (2 l)), same scheme with
+// numerator 2 O + l and denominator 2 l.
 template <int D, int L>
 __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* Orow, int g, bool round_nearest) {
     constexpr int TB = D / 32;
-    // floor((2 O + l) / (2 l)) for nearest: numerator 2 O + l, denominator 2 l
-    const unsigned den = round_nearest ? 2u * (unsigned)st.l : (unsigned)st.l;
+    static_assert(L == 16 || L == 20, "quotient must be byte aligned");
+    const int rs = round_nearest ? 1 : 0;
     const bool empty = st.l == 0;
-    const unsigned dsafe = empty ? 1u : den;
+    const unsigned dsafe = empty ? 1u : ((unsigned)st.l << rs);
     const int z = L - (32 - __clz((int)(dsafe - 1)));          // dsafe << z in (2^(L-1), 2^L]
     const unsigned dn = dsafe << z;
     const unsigned R = recip_ceil<L>(dn);
-    const int bias_u = (int)(128u * dsafe) + (round_nearest ? st.l : 0);
+    const int bias_z = (int)((128u * dsafe + (round_nearest ? (unsigned)st.l : 0u)) << z);
     const int u_max = (int)(256u * dn) - 1;
-    const int num_mul = round_nearest ? 2 : 1;
+    const int zz = z + rs;
 #pragma unroll
     for (int t = 0; t < TB; ++t)
 #pragma unroll
@@ -268,17 +293,11 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
             unsigned hi[4];
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const int o = st.acc[t][4 * a4 + b];
-                int u = (o * num_mul + bias_u) << z;
+                int u = (st.acc[t][4 * a4 + b] << zz) + bias_z;
                 u = min(max(u, 0), u_max);
-                hi[b] = (L <= 15) ? umulhi24((unsigned)u, R) : __umulhi((unsigned)u, R);
+                hi[b] = __umulhi((unsigned)u, R);
             }
-            constexpr unsigned sh = 2 * L + 8 - 32;     // quotient = hi >> sh, in [0, 255]
-            unsigned word = shr_into_byte<0>(0u, sh, hi[0]);
-            word = shr_into_byte<1>(word, sh, hi[1]);
-            word = shr_into_byte<2>(word, sh, hi[2]);
-            word = shr_into_byte<3>(word, sh, hi[3]);
-            word ^= 0x80808080u;
+            unsigned word = pack_byte<(2 * L + 8 - 32) / 8>(hi[0], hi[1], hi[2], hi[3]) ^ 0x80808080u;
             if (empty) word = 0;
             *(unsigned*)(Orow + 32 * t + 8 * a4 + 4 * g) = word;
         }
@@ -286,8 +305,10 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
 
 __device__ __forceinline__ ExpConst make_exp_const(const QflashKernelArgs& a) {
     ExpConst c;
-    c.k = a.x_shift; c.s_inv = a.s_inv; c.two_s_inv = 2 * a.s_inv; c.M = a.exp_mul;
-    c.p_mul = a.p_mul; c.x_floor = a.x_floor; c.p_shift = (unsigned)a.p_shift;
+    c.k = a.x_shift; c.s_inv = a.s_inv; c.x_floor = a.x_floor;
+    c.M_v = to_vgpr(a.exp_mul);
+    c.two_s_inv_v = to_vgpr(2 * a.s_inv);
+    c.p_mul_hi_v = to_vgpr(a.p_mul << (24 - a.p_shift));
     return c;
 }
 
@@ -337,7 +358,7 @@ extern __shared__ __align__(16) int8_t smem[];
 template <bool NARROW>
 constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
 
-template <int D, int BC, bool BIAS, bool NARROW>
+template <int D, int BC, bool BIAS, bool NARROW, bool KZ>
 __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
@@ -401,7 +422,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) 
     // ragged tile if the sequence does not end on a tile boundary.
     const int n_full = N / BC, rem = N - n_full * BC;
 #define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
-    process_tile<D, BC, BIAS, NARROW, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,          \
+    process_tile<D, BC, BIAS, KZ, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,              \
                                                      sV + (J_) * BC, VROW, NV_,                              \
                                                      BIAS ? bias_row + (J_) * BC : nullptr, c, a.a_mul, li, g)
     if (n_full > 0) {
@@ -414,7 +435,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) 
 #undef QF_TILE
     if (i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
-    if (NARROW && !a.out_round) normalise_store<D, 15>(st, Orow, g, false);
+    if (NARROW) normalise_store<D, 16>(st, Orow, g, a.out_round != 0);
     else normalise_store<D, 20>(st, Orow, g, a.out_round != 0);
 }
 
@@ -424,8 +445,9 @@ constexpr int kStreamWaves = 4;
 constexpr int kStreamThreads = kStreamWaves * 64;
 constexpr int kStreamRows = kStreamWaves * 32;
 
-template <int D, int BC, bool BIAS, bool NARROW>
+template <int D, int BC, bool BIAS>
 __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const QflashKernelArgs a) {
+    constexpr bool NARROW = false;   // long sequences only
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
     constexpr int VROW = BC + 16;
@@ -488,49 +510,54 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         const int n_valid = min(BC, N - c0);
         const int32_t* brow = BIAS ? bias_row + c0 : nullptr;
         if (j == 0)
-            process_tile<D, BC, BIAS, NARROW, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
         else if (n_valid == BC)
-            process_tile<D, BC, BIAS, NARROW, true, false>(st, qreg, sK, KROW, sV, VROW, BC, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, brow, c, a.a_mul, li, g);
         else
-            process_tile<D, BC, BIAS, NARROW, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
     }
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
-    if (NARROW && !a.out_round) normalise_store<D, 15>(st, Orow, g, false);
+    if (NARROW) normalise_store<D, 16>(st, Orow, g, a.out_round != 0);
     else normalise_store<D, 20>(st, Orow, g, a.out_round != 0);
 }
 
 // ------------------------------------------------------------------------------ launchers
 
-template <int D, int BC, bool BIAS, bool NARROW>
-int launch_one(const QflashKernelArgs& a, bool resident, size_t lds_bytes, int lds_limit, int threads,
-               hipStream_t stream) {
+template <int D, int BC, bool BIAS, bool NARROW, bool KZ>
+int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, int threads, hipStream_t stream) {
     const dim3 grid((unsigned)(8 * a.units_per_xcd));
-    if (resident) {
-        auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW>;
-        static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
-        if (!attr_set) {
-            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit) !=
-                hipSuccess)
-                return (int)hipGetLastError();
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(kern, grid, dim3((unsigned)threads), lds_bytes, stream, a);
-    } else {
-        hipLaunchKernelGGL((qflash_fwd_stream<D, BC, BIAS, NARROW>), grid, dim3(kStreamThreads), 0, stream, a);
+    auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW, KZ>;
+    static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit) != hipSuccess)
+            return (int)hipGetLastError();
+        attr_set = true;
     }
+    hipLaunchKernelGGL(kern, grid, dim3((unsigned)threads), lds_bytes, stream, a);
     return (int)hipGetLastError();
+}
+
+template <int D, int BC, bool BIAS>
+int launch_dbc_bias(const QflashKernelArgs& a, bool resident, size_t lds, int lds_limit, int threads, hipStream_t st) {
+    if (!resident) {
+        const dim3 grid((unsigned)(8 * a.units_per_xcd));
+        hipLaunchKernelGGL((qflash_fwd_stream<D, BC, BIAS>), grid, dim3(kStreamThreads), 0, st, a);
+        return (int)hipGetLastError();
+    }
+    const bool narrow = a.N <= 256, kz = a.x_shift == 0;
+    if (narrow) {
+        return kz ? launch_resident<D, BC, BIAS, true, true>(a, lds, lds_limit, threads, st)
+                  : launch_resident<D, BC, BIAS, true, false>(a, lds, lds_limit, threads, st);
+    }
+    return kz ? launch_resident<D, BC, BIAS, false, true>(a, lds, lds_limit, threads, st)
+              : launch_resident<D, BC, BIAS, false, false>(a, lds, lds_limit, threads, st);
 }
 
 template <int D, int BC>
 int launch_dbc(const QflashKernelArgs& a, bool resident, size_t lds, int lds_limit, int threads, hipStream_t st) {
-    const bool narrow = a.N <= 256;
-    if (a.bias) {
-        return narrow ? launch_one<D, BC, true, true>(a, resident, lds, lds_limit, threads, st)
-                      : launch_one<D, BC, true, false>(a, resident, lds, lds_limit, threads, st);
-    }
-    return narrow ? launch_one<D, BC, false, true>(a, resident, lds, lds_limit, threads, st)
-                  : launch_one<D, BC, false, false>(a, resident, lds, lds_limit, threads, st);
+    return a.bias ? launch_dbc_bias<D, BC, true>(a, resident, lds, lds_limit, threads, st)
+                  : launch_dbc_bias<D, BC, false>(a, resident, lds, lds_limit, threads, st);
 }
 
 }  // namespace
