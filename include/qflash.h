@@ -70,6 +70,18 @@ int qflash_params_from_scales(double sQ, double sK, double sV, int d, qflash_par
 int qflash_create(qflash_ctx** out, int device_id);
 
 /*
+ * Context options.  QFLASH_CFG_EXP_TABLE (default 1): 1 lets the kernel read the int8 weight of a
+ * score (Algorithm 2 followed by Eq. 10) from a table of that same function held in LDS when the
+ * table is small enough (about 8 * s_inv / 2^x_shift bytes, up to 40 KiB); 0 always evaluates
+ * Algorithm 2 arithmetically.  Both give identical bits.  A table is built on the GPU, once per
+ * set of constants and stream (first call with them; up to 32 per context, never rewritten; when
+ * they are used up later constants take the arithmetic mode).
+ * Errors: NULL, CTX, PARAM (unknown key or value).
+ */
+#define QFLASH_CFG_EXP_TABLE 1
+int qflash_configure(qflash_ctx* ctx, int key, int value);
+
+/*
  * One fused attention forward pass (Algorithm 1), enqueued on `hip_stream`; returns without
  * waiting for the GPU.
  *
@@ -90,7 +102,9 @@ int qflash_create(qflash_ctx** out, int device_id);
  *   hip_stream  a hipStream_t of the context's device (NULL = the default stream).
  *
  * All buffers must stay valid until the stream has executed the work.  Calls on one context
- * from several host threads are allowed (the context holds no per-call state).
+ * from several host threads are allowed (the context's table cache is guarded by a lock).  The
+ * first call with new constants on a stream also enqueues a small table-building kernel on that
+ * stream; a stream handle must not be reused for a new stream while its context lives.
  * Errors: CTX, NULL, SHAPE, TILE, PARAM, ALIGN, DEVICE, LAUNCH.  On error nothing is enqueued.
  */
 int qflash_attention(qflash_ctx* ctx,

@@ -6,6 +6,6 @@ CPU or PyTorch fallback; if the library has not been built, importing ``binding`
 """
 from .binding import (  # noqa: F401
     QFlashError, QFlashParams, Context, library_path, load_library,
-    qflash_params_from_scales, qflash_create, qflash_attention, qflash_destroy, qflash_strerror,
-    EXCLUDED, ERR,
+    qflash_params_from_scales, qflash_create, qflash_configure, qflash_attention, qflash_destroy,
+    qflash_strerror, EXCLUDED, ERR, CFG_EXP_TABLE,
 )

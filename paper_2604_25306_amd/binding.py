@@ -14,8 +14,10 @@ EXCLUDED = -(1 << 31)
 ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, "LAUNCH": -6,
        "CTX": -7, "ALIGN": -8}
 
-EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_attention", "qflash_destroy",
-           "qflash_strerror"]
+EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
+           "qflash_destroy", "qflash_strerror"]
+
+CFG_EXP_TABLE = 1
 
 
 class QFlashError(RuntimeError):
@@ -57,6 +59,8 @@ def load_library():
         lib.qflash_create.argtypes = [ctypes.POINTER(vp), ci]
         lib.qflash_attention.restype = ci
         lib.qflash_attention.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
+        lib.qflash_configure.restype = ci
+        lib.qflash_configure.argtypes = [vp, ci, ci]
         lib.qflash_destroy.restype = ci
         lib.qflash_destroy.argtypes = [vp]
         lib.qflash_strerror.restype = ctypes.c_char_p
@@ -85,6 +89,12 @@ def qflash_create(device_id: int = 0) -> int:
     if rc != 0:
         raise QFlashError(rc, "qflash_create")
     return h.value
+
+
+def qflash_configure(ctx: int, key: int, value: int) -> None:
+    rc = load_library().qflash_configure(ctypes.c_void_p(ctx), int(key), int(value))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_configure")
 
 
 def qflash_destroy(ctx: Optional[int]) -> None:
@@ -130,6 +140,9 @@ class Context:
 
     def __init__(self, device_id: int = 0):
         self.handle = qflash_create(device_id)
+
+    def configure(self, key: int, value: int):
+        qflash_configure(self.handle, key, value)
 
     def attention(self, Q, K, V, O, params, kv_tile, bias=None, stream=None):
         qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)

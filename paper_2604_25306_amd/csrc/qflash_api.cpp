@@ -13,9 +13,25 @@
 #include "qflash.h"
 #include "qflash_internal.h"
 
+// One immutable weight table.  A slot is written once (by a kernel enqueued on `stream`) and only
+// ever used by launches on that same stream, so stream order alone makes it safe; it is never
+// rewritten, so captured graphs and in-flight kernels can keep reading it.
+struct TableSlot {
+    int32_t key[5];   // x_shift, s_inv, exp_mul, p_mul, p_shift
+    void* stream;
+    int n, n_padded, x_p;
+};
+
+constexpr int kTableSlots = 32;
+constexpr int kTableMaxBytes = 40 * 1024;
+
 struct qflash_ctx {
     int device;
-    int lds_limit;   // LDS bytes one workgroup may allocate on this device
+    int lds_limit;        // LDS bytes one workgroup may allocate on this device
+    int use_table;        // QFLASH_CFG_EXP_TABLE
+    uint8_t* tables;      // device, kTableSlots x kTableMaxBytes
+    int n_slots;          // slots in use
+    TableSlot slots[kTableSlots];
 };
 
 namespace {
@@ -116,6 +132,16 @@ extern "C" int qflash_create(qflash_ctx** out, int device_id) {
         lds = 64 * 1024;
     }
     c->lds_limit = lds;
+    c->use_table = 1;
+    c->n_slots = 0;
+    c->tables = nullptr;
+    int cur = -1;
+    const bool switched = hipGetDevice(&cur) == hipSuccess && cur != device_id && hipSetDevice(device_id) == hipSuccess;
+    if (hipMalloc((void**)&c->tables, (size_t)kTableSlots * kTableMaxBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        c->tables = nullptr;   // the arithmetic mode needs no tables
+    }
+    if (switched) (void)hipSetDevice(cur);
     {
         std::lock_guard<std::mutex> lk(g_mu);
         live_contexts().insert(c);
@@ -132,7 +158,19 @@ extern "C" int qflash_destroy(qflash_ctx* ctx) {
         if (it == live_contexts().end()) return QFLASH_ERR_CTX;
         live_contexts().erase(it);
     }
+    if (ctx->tables) {
+        if (hipFree(ctx->tables) != hipSuccess) (void)hipGetLastError();
+    }
     delete ctx;
+    return QFLASH_OK;
+}
+
+extern "C" int qflash_configure(qflash_ctx* ctx, int key, int value) {
+    if (!ctx) return QFLASH_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+    if (key != QFLASH_CFG_EXP_TABLE || (value != 0 && value != 1)) return QFLASH_ERR_PARAM;
+    ctx->use_table = value;
     return QFLASH_OK;
 }
 
@@ -186,7 +224,43 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
         (void)hipGetLastError();
         return QFLASH_ERR_DEVICE;
     }
-    const int rc = qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+    // Look-up mode: find (or build, once, on this stream) the weight table of these constants.
+    a.lut = nullptr; a.lut_bytes = 0; a.lut_xp = 0;
+    int rc = 0;
+    {
+        // weight is 0 at and below -8 octaves: x_p = ceil(8 s_inv / 2^k)
+        const int64_t x_p = (8 * (int64_t)p->s_inv + ((int64_t)1 << p->x_shift) - 1) >> p->x_shift;
+        const int n = (int)x_p + 1, n_padded = (n + 15) & ~15;
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (ctx->use_table && ctx->tables && a.resident && n_padded <= kTableMaxBytes &&
+            qflash_table_fits(N, d, n_padded, lds_limit)) {
+            const int32_t key[5] = {p->x_shift, p->s_inv, p->exp_mul, p->p_mul, p->p_shift};
+            int slot = -1;
+            for (int i = 0; i < ctx->n_slots; ++i)
+                if (ctx->slots[i].stream == hip_stream && std::memcmp(ctx->slots[i].key, key, sizeof key) == 0) {
+                    slot = i;
+                    break;
+                }
+            if (slot < 0 && ctx->n_slots < kTableSlots) {
+                // The builder is enqueued under the lock, so no other host thread can enqueue a
+                // reader of this slot on the same stream ahead of it.
+                uint8_t* tbl = ctx->tables + (size_t)ctx->n_slots * kTableMaxBytes;
+                rc = qflash_launch_build_table(tbl, n, n_padded, (int)x_p, a, hip_stream);
+                if (rc == 0) {
+                    slot = ctx->n_slots++;
+                    TableSlot& t = ctx->slots[slot];
+                    std::memcpy(t.key, key, sizeof key);
+                    t.stream = hip_stream; t.n = n; t.n_padded = n_padded; t.x_p = (int)x_p;
+                }
+            }
+            if (slot >= 0) {
+                a.lut = ctx->tables + (size_t)slot * kTableMaxBytes;
+                a.lut_bytes = n_padded;
+                a.lut_xp = (int)x_p;
+            }
+        }
+    }
+    if (rc == 0) rc = qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
     return QFLASH_OK;

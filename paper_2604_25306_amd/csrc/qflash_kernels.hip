@@ -154,12 +154,18 @@ struct RowState {
 
 // One KV tile for one wavefront.  sK: K rows of the tile (row pitch KROW), sV: V^T with the tile's
 // columns starting at column 0 (row pitch VROW).  n_valid = number of real kv rows in the tile.
-template <int D, int BC, bool BIAS, bool KZ, bool FULL, bool FIRST>
+// XM selects how the int8 weight of a score is obtained: kExpShift (Algorithm 2 + Eq. 10 in the
+// ALUs, any x_shift), kExpShift0 (the same, x_shift == 0) or kExpTable (one LDS look-up in a table
+// of the same function, see qflash_build_table).
+enum { kExpShift = 0, kExpShift0 = 1, kExpTable = 2 };
+
+template <int D, int BC, bool BIAS, int XM, bool FULL, bool FIRST>
 __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
-                                            const int8_t* sV, int VROW, int n_valid_rt,
+                                            const int8_t* sV, int VROW, int n_valid_rt, const uint8_t* sT, int x_p,
                                             const int32_t* bias_row /* + c0 */, const ExpConst& c,
                                             int a_mul, int li, int g) {
     constexpr int KSTEPS = D / 32, TB = D / 32, KB = BC / 32;
+    constexpr bool KZ = XM == kExpShift0;
     // FULL: the tile has all BC kv rows, every "is this group inside the sequence" test below is
     // true at compile time and the tile is one straight line of code.
     const int n_valid = FULL ? BC : n_valid_rt;
@@ -213,45 +219,83 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
     m_new = max(m_new, other_half(m_new));
     const int lo = m_new + c.x_floor;
     const int m2 = m_new - 2 * c.s_inv;
+    const int tbase = m_new - x_p;   // table index of a score s is s - tbase
     // ---- step 4: max-offset factor alpha, brought to 16 fractional bits (kept as alpha16 << 14)
     int alpha14 = 0;
     if (!FIRST) {
         const int a_hat = shift_exp2<KZ>(max(st.m, lo), m_new, m2, c);
         alpha14 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536) << 14;
     }
-    // ---- steps 5,6,7: score intensity, requantisation to int8 (Eq. 10), row sum
     v4i pk[KB];
     int rowsum = 0;
+    if (XM == kExpTable) {
+        // ---- steps 5,6 by table: issue every look-up of the tile, rescale the accumulators while
+        //      the LDS answers, then pack.  Index 0 of the table is the weight 0 of everything at
+        //      or below -x_p (excluded scores included).
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        pk[kb] = v4i{0, 0, 0, 0};
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4)
-            if (32 * kb + 8 * a4 < n_valid) {
-                unsigned pr[4];
+            for (int a4 = 0; a4 < 4; ++a4)
+                if (32 * kb + 8 * a4 < n_valid) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int y = shift_exp2<KZ>(max(s[kb][4 * a4 + b], lo), m_new, m2, c);
-                    pr[b] = (unsigned)__mul24(y, c.p_mul_hi_v);       // Eq. 10, result in byte 3
+                    for (int b = 0; b < 4; ++b) s[kb][4 * a4 + b] = sT[max(s[kb][4 * a4 + b] - tbase, 0)];
                 }
-                const unsigned w = pack_byte3(pr[0], pr[1], pr[2], pr[3]);
-                pk[kb][a4] = (int)w;
-                rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
-            }
-    }
-    rowsum += other_half(rowsum);
-    // Keep the phases apart: letting the scheduler overlap the rescale below with the element-wise
-    // work above only lengthens live ranges (spills) without gaining issue slots.
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- steps 9,10: ScaleRelease of the running denominator and numerator
-    if (FIRST) {
-        st.l = rowsum;
+        __builtin_amdgcn_sched_barrier(0);
+        if (!FIRST) {
+            st.l = scale_release(st.l, alpha14);
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            pk[kb] = v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int a4 = 0; a4 < 4; ++a4)
+                if (32 * kb + 8 * a4 < n_valid) {
+                    const unsigned w = (unsigned)s[kb][4 * a4] | ((unsigned)s[kb][4 * a4 + 1] << 8) |
+                                       ((unsigned)s[kb][4 * a4 + 2] << 16) | ((unsigned)s[kb][4 * a4 + 3] << 24);
+                    pk[kb][a4] = (int)w;
+                    rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);   // step 7
+                }
+        }
+        rowsum += other_half(rowsum);
+        st.l += rowsum;                                                                    // step 9
     } else {
-        st.l = scale_release(st.l, alpha14) + rowsum;
+        // ---- steps 5,6,7: score intensity, requantisation to int8 (Eq. 10), row sum
 #pragma unroll
-        for (int t = 0; t < TB; ++t)
+        for (int kb = 0; kb < KB; ++kb) {
+            pk[kb] = v4i{0, 0, 0, 0};
 #pragma unroll
-            for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14);
+            for (int a4 = 0; a4 < 4; ++a4)
+                if (32 * kb + 8 * a4 < n_valid) {
+                    unsigned pr[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int y = shift_exp2<KZ>(max(s[kb][4 * a4 + b], lo), m_new, m2, c);
+                        pr[b] = (unsigned)__mul24(y, c.p_mul_hi_v);       // Eq. 10, result in byte 3
+                    }
+                    const unsigned w = pack_byte3(pr[0], pr[1], pr[2], pr[3]);
+                    pk[kb][a4] = (int)w;
+                    rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
+                }
+        }
+        rowsum += other_half(rowsum);
+        // Keep the phases apart: letting the scheduler overlap the rescale below with the
+        // element-wise work above only lengthens live ranges (spills) without gaining issue slots.
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- steps 9,10: ScaleRelease of the running denominator and numerator
+        if (FIRST) {
+            st.l = rowsum;
+        } else {
+            st.l = scale_release(st.l, alpha14) + rowsum;
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     // ---- step 8: O^T += V_j^T P^T
@@ -358,15 +402,19 @@ extern __shared__ __align__(16) int8_t smem[];
 template <bool NARROW>
 constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
 
-template <int D, int BC, bool BIAS, bool NARROW, bool KZ>
+template <int D, int BC, bool BIAS, bool NARROW, int XM>
 __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
     const int N = a.N;
     const int npad = (N + 31) & ~31;
     const int VROW = npad + 16;
-    int8_t* sK = smem;                       // [npad][KROW]
-    int8_t* sV = smem + (size_t)npad * KROW; // [D][VROW]
+    // LDS: [weight table, lut_bytes (table mode only)] [K: npad x KROW] [V^T: D x VROW].  The table
+    // sits at offset 0 so that its index is the LDS address.
+    const int tbytes = XM == kExpTable ? a.lut_bytes : 0;
+    const uint8_t* sT = (const uint8_t*)smem;
+    int8_t* sK = smem + tbytes;
+    int8_t* sV = sK + (size_t)npad * KROW;
 
     const int wg = blockIdx.x;
     const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
@@ -385,6 +433,9 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) 
     const int8_t* Kh = a.K + head_off;
     const int8_t* Vh = a.V + head_off;
 
+    // ---- stage the weight table (L2-resident, shared by every workgroup of the launch)
+    if (XM == kExpTable)
+        for (int ch = tid; ch < tbytes / 16; ch += nthr) *(v4i*)(smem + 16 * ch) = *(const v4i*)(a.lut + 16 * ch);
     // ---- stage the whole K (row-major) and V^T (permuted columns) of this head
     for (int ch = tid; ch < npad * (D / 16); ch += nthr) {
         const int r = ch / (D / 16), c16 = ch % (D / 16);
@@ -422,8 +473,8 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) 
     // ragged tile if the sequence does not end on a tile boundary.
     const int n_full = N / BC, rem = N - n_full * BC;
 #define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
-    process_tile<D, BC, BIAS, KZ, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,              \
-                                                     sV + (J_) * BC, VROW, NV_,                              \
+    process_tile<D, BC, BIAS, XM, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,              \
+                                                     sV + (J_) * BC, VROW, NV_, sT, a.lut_xp,                \
                                                      BIAS ? bias_row + (J_) * BC : nullptr, c, a.a_mul, li, g)
     if (n_full > 0) {
         QF_TILE(true, true, 0, BC);
@@ -510,11 +561,11 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         const int n_valid = min(BC, N - c0);
         const int32_t* brow = BIAS ? bias_row + c0 : nullptr;
         if (j == 0)
-            process_tile<D, BC, BIAS, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, kExpShift, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, nullptr, 0, brow, c, a.a_mul, li, g);
         else if (n_valid == BC)
-            process_tile<D, BC, BIAS, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, kExpShift, true, false>(st, qreg, sK, KROW, sV, VROW, BC, nullptr, 0, brow, c, a.a_mul, li, g);
         else
-            process_tile<D, BC, BIAS, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, kExpShift, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, nullptr, 0, brow, c, a.a_mul, li, g);
     }
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
@@ -524,10 +575,28 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
 
 // ------------------------------------------------------------------------------ launchers
 
-template <int D, int BC, bool BIAS, bool NARROW, bool KZ>
+// Weight table for the look-up mode: T[i] = int8 weight (Algorithm 2 + Eq. 10) of the score
+// difference x = i - x_p, for i in [0, x_p]; x_p is chosen on the host so that the weight is 0 at
+// and below -x_p.  Entries [n, n_padded) are 0 and never addressed.  Built by the same device
+// functions the arithmetic mode uses, so the two modes cannot disagree.
+__global__ __launch_bounds__(256) void qflash_build_table(uint8_t* tbl, int n, int n_padded, int x_p,
+                                                          const QflashKernelArgs a) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_padded) return;
+    const ExpConst c = make_exp_const(a);
+    unsigned p = 0;
+    if (i < n) {
+        const int x = max(i - x_p, a.x_floor);
+        const int y = shift_exp2<false>(x, 0, -2 * a.s_inv, c);
+        p = ((unsigned)__mul24(y, c.p_mul_hi_v)) >> 24;
+    }
+    tbl[i] = (uint8_t)p;
+}
+
+template <int D, int BC, bool BIAS, bool NARROW, int XM>
 int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, int threads, hipStream_t stream) {
     const dim3 grid((unsigned)(8 * a.units_per_xcd));
-    auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW, KZ>;
+    auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW, XM>;
     static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit) != hipSuccess)
@@ -538,6 +607,13 @@ int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, 
     return (int)hipGetLastError();
 }
 
+template <int D, int BC, bool BIAS, bool NARROW>
+int launch_mode(const QflashKernelArgs& a, size_t lds, int lds_limit, int threads, hipStream_t st) {
+    if (a.lut) return launch_resident<D, BC, BIAS, NARROW, kExpTable>(a, lds, lds_limit, threads, st);
+    if (a.x_shift == 0) return launch_resident<D, BC, BIAS, NARROW, kExpShift0>(a, lds, lds_limit, threads, st);
+    return launch_resident<D, BC, BIAS, NARROW, kExpShift>(a, lds, lds_limit, threads, st);
+}
+
 template <int D, int BC, bool BIAS>
 int launch_dbc_bias(const QflashKernelArgs& a, bool resident, size_t lds, int lds_limit, int threads, hipStream_t st) {
     if (!resident) {
@@ -545,13 +621,8 @@ int launch_dbc_bias(const QflashKernelArgs& a, bool resident, size_t lds, int ld
         hipLaunchKernelGGL((qflash_fwd_stream<D, BC, BIAS>), grid, dim3(kStreamThreads), 0, st, a);
         return (int)hipGetLastError();
     }
-    const bool narrow = a.N <= 256, kz = a.x_shift == 0;
-    if (narrow) {
-        return kz ? launch_resident<D, BC, BIAS, true, true>(a, lds, lds_limit, threads, st)
-                  : launch_resident<D, BC, BIAS, true, false>(a, lds, lds_limit, threads, st);
-    }
-    return kz ? launch_resident<D, BC, BIAS, false, true>(a, lds, lds_limit, threads, st)
-              : launch_resident<D, BC, BIAS, false, false>(a, lds, lds_limit, threads, st);
+    return a.N <= 256 ? launch_mode<D, BC, BIAS, true>(a, lds, lds_limit, threads, st)
+                      : launch_mode<D, BC, BIAS, false>(a, lds, lds_limit, threads, st);
 }
 
 template <int D, int BC>
@@ -562,16 +633,18 @@ int launch_dbc(const QflashKernelArgs& a, bool resident, size_t lds, int lds_lim
 
 }  // namespace
 
-// LDS bytes of the resident kernel for a head of N rows, or 0 if it does not fit.
-static size_t resident_lds_bytes(int N, int d, int lds_limit) {
+// LDS bytes of the resident kernel for a head of N rows (K, V^T and the weight table), or 0 if
+// they do not fit.
+static size_t resident_lds_bytes(int N, int d, int table_bytes, int lds_limit) {
     const size_t npad = (size_t)((N + 31) & ~31);
-    const size_t bytes = npad * (size_t)(d + 16) + (size_t)d * (npad + 16);
+    const size_t bytes = npad * (size_t)(d + 16) + (size_t)d * (npad + 16) + (size_t)table_bytes;
     return bytes <= (size_t)lds_limit ? bytes : 0;
 }
 
 int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* a) {
-    const size_t lds = resident_lds_bytes(N, d, lds_limit);
-    if (lds != 0) {
+    (void)kv_tile;
+    a->resident = resident_lds_bytes(N, d, 0, lds_limit) != 0;
+    if (a->resident) {
         const int nblk = (N + 31) / 32;
         const int max_waves = N <= 256 ? resident_max_waves<true>() : resident_max_waves<false>();
         const int tiles = (nblk + max_waves - 1) / max_waves;
@@ -584,14 +657,26 @@ int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* 
     return 0;
 }
 
+int qflash_table_fits(int N, int d, int table_bytes, int lds_limit) {
+    // keep two workgroups per CU when the sequence is short enough for that to matter
+    const int budget = N <= 256 ? lds_limit / 2 : lds_limit;
+    return resident_lds_bytes(N, d, table_bytes, budget) != 0;
+}
+
+int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashKernelArgs& a, void* stream) {
+    hipLaunchKernelGGL(qflash_build_table, dim3((unsigned)((n_padded + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, tbl, n, n_padded, x_p, a);
+    return (int)hipGetLastError();
+}
+
 int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = resident_lds_bytes(a.N, d, lds_limit);
-    const bool resident = lds != 0;
-    const int threads = resident ? 2 * a.rows_per_wg : kStreamThreads;
-    if (d == 64 && kv_tile == 64) return launch_dbc<64, 64>(a, resident, lds, lds_limit, threads, st);
-    if (d == 64 && kv_tile == 128) return launch_dbc<64, 128>(a, resident, lds, lds_limit, threads, st);
-    if (d == 32 && kv_tile == 64) return launch_dbc<32, 64>(a, resident, lds, lds_limit, threads, st);
-    if (d == 32 && kv_tile == 128) return launch_dbc<32, 128>(a, resident, lds, lds_limit, threads, st);
+    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.lut ? a.lut_bytes : 0, lds_limit) : 0;
+    if (a.resident && lds == 0) return (int)hipErrorInvalidValue;
+    const int threads = a.resident ? 2 * a.rows_per_wg : kStreamThreads;
+    if (d == 64 && kv_tile == 64) return launch_dbc<64, 64>(a, a.resident, lds, lds_limit, threads, st);
+    if (d == 64 && kv_tile == 128) return launch_dbc<64, 128>(a, a.resident, lds, lds_limit, threads, st);
+    if (d == 32 && kv_tile == 64) return launch_dbc<32, 64>(a, a.resident, lds, lds_limit, threads, st);
+    if (d == 32 && kv_tile == 128) return launch_dbc<32, 128>(a, a.resident, lds, lds_limit, threads, st);
     return (int)hipErrorInvalidValue;
 }

@@ -15,13 +15,16 @@ from workloads import make_workload, quantize_per_tensor, EXCLUDED
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def gpu():
+@pytest.fixture(scope="module", params=["table", "arith"])
+def gpu(request):
+    """Every parity case runs twice: with the LDS weight table allowed (the default; the library
+    still computes arithmetically where no table fits) and with it switched off."""
     import torch
     import paper_2604_25306_amd as qf
     assert torch.cuda.is_available(), "these tests need a GPU"
     qf.load_library()                      # raises if the HIP library has not been built
     ctx = qf.Context(0)
+    ctx.configure(qf.CFG_EXP_TABLE, 1 if request.param == "table" else 0)
     yield torch, qf, ctx
     ctx.close()
 
