@@ -233,7 +233,7 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
         const int n = (int)x_p + 1, n_padded = (n + 15) & ~15;
         std::lock_guard<std::mutex> lk(g_mu);
         if (ctx->use_table && ctx->tables && a.resident && n_padded <= kTableMaxBytes &&
-            qflash_table_fits(N, d, n_padded, lds_limit)) {
+            qflash_table_fits(N, d, a.rows_per_wg, n_padded, lds_limit)) {
             const int32_t key[5] = {p->x_shift, p->s_inv, p->exp_mul, p->p_mul, p->p_shift};
             int slot = -1;
             for (int i = 0; i < ctx->n_slots; ++i)

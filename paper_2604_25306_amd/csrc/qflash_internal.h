@@ -32,8 +32,8 @@ int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_
 // lds_limit = LDS bytes one workgroup may use on this device.
 int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);
 
-// 1 if the resident kernel can also hold a weight table of table_bytes in LDS.
-int qflash_table_fits(int N, int d, int table_bytes, int lds_limit);
+// 1 if the resident kernel can also hold a weight table of table_bytes in LDS and copying it pays.
+int qflash_table_fits(int N, int d, int rows_per_wg, int table_bytes, int lds_limit);
 
 // Enqueue the kernel that fills a weight table of n entries (n_padded bytes) for args' constants.
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashKernelArgs& args, void* stream);

@@ -219,7 +219,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
     m_new = max(m_new, other_half(m_new));
     const int lo = m_new + c.x_floor;
     const int m2 = m_new - 2 * c.s_inv;
-    const int tbase = m_new - x_p;   // table index of a score s is s - tbase
+    const int x_p_v = XM == kExpTable ? to_vgpr(x_p) : 0;
     // ---- step 4: max-offset factor alpha, brought to 16 fractional bits (kept as alpha16 << 14)
     int alpha14 = 0;
     if (!FIRST) {
@@ -238,7 +238,14 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
             for (int a4 = 0; a4 < 4; ++a4)
                 if (32 * kb + 8 * a4 < n_valid) {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) s[kb][4 * a4 + b] = sT[max(s[kb][4 * a4 + b] - tbase, 0)];
+                    for (int b = 0; b < 4; ++b) {
+                        // index = max(x_p - (m - s), 0): two fast-class subtractions, the second one
+                        // saturating at 0 (m - s >= 0; excluded scores give a huge difference)
+                        const unsigned dist = (unsigned)(m_new - s[kb][4 * a4 + b]);
+                        unsigned idx;
+                        asm("v_sub_u32_e64 %0, %1, %2 clamp" : "=v"(idx) : "v"(x_p_v), "v"(dist));
+                        s[kb][4 * a4 + b] = sT[idx];
+                    }
                 }
         __builtin_amdgcn_sched_barrier(0);
         if (!FIRST) {
@@ -657,7 +664,10 @@ int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* 
     return 0;
 }
 
-int qflash_table_fits(int N, int d, int table_bytes, int lds_limit) {
+int qflash_table_fits(int N, int d, int rows_per_wg, int table_bytes, int lds_limit) {
+    // Every workgroup copies the table into its LDS: worth it only if the workgroup then reads
+    // at least about one weight per table byte.
+    if ((long long)rows_per_wg * N < (long long)table_bytes) return 0;
     // keep two workgroups per CU when the sequence is short enough for that to matter
     const int budget = N <= 256 ? lds_limit / 2 : lds_limit;
     return resident_lds_bytes(N, d, table_bytes, budget) != 0;
