@@ -410,7 +410,7 @@ template <bool NARROW>
 constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
 
 template <int D, int BC, bool BIAS, bool NARROW, int XM>
-__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? 4 : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
+__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
     const int N = a.N;
