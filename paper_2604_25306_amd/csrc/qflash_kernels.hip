@@ -128,19 +128,27 @@ __device__ __forceinline__ int scale_release(int x, int alpha14) {
     return __mulhi(x4, alpha14);
 }
 
-// ceil(2^(2L+8) / d) for d in (2^(L-1), 2^L] by restoring division: integer only, L+9 steps.
+// R = ceil(2^(2L+8) / d) for d in (2^(L-1), 2^L], L = 16 or 20, in integer arithmetic only:
+// Newton's iteration for 1/d on 32-bit fixed point (32-bit multiply-high is full rate here),
+// then one exact remainder step.  With d31 = d << (31-L) in (2^30, 2^31] and x ~ 2^62 / d31:
+//   x0 = (48/17 - 32/17 * d31/2^31) * 2^31,   x <- (x * (2^31 - (d31 * x >> 32)) >> 32) << 2   (3 times)
+// q = x >> (23-L) is floor((2^(2L+8) - 1) / d) to within +-1 for every d of both ranges (checked by
+// enumerating all of them; tests/test_host_logic.py repeats that); the low 32 bits of the remainder
+// (2^(2L+8) - 1) - q d decide the correction, and R = q + 1.
 template <int L>
 __device__ __forceinline__ unsigned recip_ceil(unsigned d) {
-    unsigned rem = 1u << (L - 1), q = 0;
+    const unsigned d31 = d << (31 - L);
+    unsigned x = (3031741621u - __umulhi(4042322161u, d31)) << 1;
 #pragma unroll
-    for (int it = 0; it < L + 9; ++it) {
-        rem <<= 1;
-        const unsigned sub = rem - d;
-        const bool ge = rem >= d;
-        rem = ge ? sub : rem;
-        q = (q << 1) | (ge ? 1u : 0u);
+    for (int it = 0; it < 3; ++it) {
+        const unsigned f = 0x80000000u - __umulhi(d31, x);
+        x = __umulhi(x, f) << 2;
     }
-    return q + (rem != 0 ? 1u : 0u);
+    unsigned q = x >> (23 - L);
+    const int rem = (int)(0xffffffffu - q * d);
+    if (rem < 0) q -= 1;
+    else if ((unsigned)rem >= d) q += 1;
+    return q + 1;
 }
 
 // ---------------------------------------------------------------------- per-wavefront state

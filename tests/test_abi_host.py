@@ -85,3 +85,5 @@ def test_context_errors_without_gpu(lib):
     h = ctypes.c_void_p()
     rc = lib.qflash_create(ctypes.byref(h), 9999)
     assert rc == qf.ERR["DEVICE"] and not h.value
+    assert lib.qflash_configure(None, qf.CFG_EXP_TABLE, 1) == qf.ERR["NULL"]
+    assert lib.qflash_configure(bogus, qf.CFG_EXP_TABLE, 1) == qf.ERR["CTX"]

@@ -206,6 +206,27 @@ def test_stream_determinism_and_full_overwrite(gpu):
     assert np.array_equal(a, ref) and np.array_equal(b, ref) and np.array_equal(c, ref)
 
 
+def test_table_cache_many_constants_and_streams(gpu):
+    """More distinct constants than the context has table slots (later ones fall back to the
+    arithmetic mode), and the same constants on two streams (each builds its own table)."""
+    torch, qf, ctx = gpu
+    rng = np.random.default_rng(12)
+    shape = (1, 2, 100, 64)
+    Q = rng.integers(-127, 128, size=shape).astype(np.int8)
+    K = rng.integers(-127, 128, size=shape).astype(np.int8)
+    V = rng.integers(-127, 128, size=shape).astype(np.int8)
+    s2 = torch.cuda.Stream()
+    for j in range(40):
+        p = oracle.derive_params(0.03 + 0.001 * j, 0.04, 64)
+        ref = oracle.qflash_attention(Q, K, V, p, 64)
+        assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64), ref), j
+        if j < 3:
+            assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64, stream=s2.cuda_stream), ref), j
+    # and the first constants still work after the cache is full
+    p = oracle.derive_params(0.03, 0.04, 64)
+    assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64), oracle.qflash_attention(Q, K, V, p, 64))
+
+
 def test_error_codes_on_gpu(gpu):
     torch, qf, ctx = gpu
     lib = qf.load_library()
@@ -235,6 +256,8 @@ def test_error_codes_on_gpu(gpu):
         bad = qf.QFlashParams(*p.astuple())
         setattr(bad, field, val)
         assert call(par=bad) == qf.ERR["PARAM"], field
+    assert lib.qflash_configure(h, 99, 1) == qf.ERR["PARAM"]
+    assert lib.qflash_configure(h, qf.CFG_EXP_TABLE, 2) == qf.ERR["PARAM"]
     torch.cuda.synchronize()
     # context life cycle
     h2 = qf.qflash_create(0)

@@ -1,0 +1,88 @@
+"""Integer identities the GPU kernels rely on, checked on the CPU by enumeration (no GPU).
+
+These do not test kernel code (that is what the GPU parity tests do); they establish the facts the
+kernel comments state: the Newton reciprocal is exact for every divisor it can meet, the
+reciprocal-multiply normalisation equals floor division, the folded form of Algorithm 2 equals
+the printed one, and the 32-bit ScaleRelease equals the 64-bit definition.
+"""
+import numpy as np
+
+M32 = (1 << 32) - 1
+C1 = round(48 / 17 * 2 ** 30)
+C2 = round(16 / 17 * 2 ** 32)
+
+
+def recip_ceil(dn, L):
+    """ceil(2^(2L+8) / dn) for dn in (2^(L-1), 2^L]: the kernel's algorithm on uint32 semantics."""
+    dn = np.asarray(dn, dtype=object)
+    d31 = (dn << (31 - L)) & M32
+    x = (C1 - ((C2 * d31) >> 32)) << 1
+    assert max(x) <= M32 and min(x) >= 0
+    for _ in range(3):
+        f = (1 << 31) - ((d31 * x) >> 32)
+        assert min(f) >= 0
+        x = ((x * f) >> 32) << 2
+        assert max(x) <= M32
+    q = x >> (23 - L)
+    rem = (M32 - ((q * dn) & M32)) & M32
+    rem = np.array([r - (1 << 32) if r >= (1 << 31) else r for r in rem], dtype=object)
+    q = np.where(rem < 0, q - 1, np.where(rem >= dn, q + 1, q))
+    return q + 1
+
+
+def test_constants():
+    assert (C1, C2) == (3031741621, 4042322161)
+
+
+def test_newton_reciprocal_exact_for_every_divisor():
+    for L in (16, 20):
+        dn = np.arange((1 << (L - 1)) + 1, (1 << L) + 1, dtype=object)
+        K = 2 * L + 8
+        assert np.all(recip_ceil(dn, L) == -((-(1 << K)) // dn)), L
+
+
+def test_reciprocal_multiply_is_floor_division():
+    """floor(u * R / 2^(2L+8)) == u // d for every u < 256 d (sampled u, many d, both widths)."""
+    rng = np.random.default_rng(0)
+    for L in (16, 20):
+        K = 2 * L + 8
+        d = rng.integers((1 << (L - 1)) + 1, (1 << L) + 1, size=2000).astype(object)
+        d[:2] = [(1 << (L - 1)) + 1, 1 << L]
+        R = recip_ceil(d, L)
+        for _ in range(20):
+            u = np.array([int(rng.integers(0, 256 * int(x))) for x in d], dtype=object)
+            assert np.all((u * R) >> K == u // d)
+        for u in (np.zeros_like(d), 256 * d - 1, 255 * d, 255 * d - 1):
+            assert np.all((u * R) >> K == u // d)
+
+
+def test_biased_quotient_equals_saturated_floor_division():
+    """byte(floor((O + 128 l) clamped / l)) ^ 0x80 == clamp(floor(O / l), -128, 127)."""
+    rng = np.random.default_rng(1)
+    for _ in range(20000):
+        l = int(rng.integers(1, 1 << 19))
+        o = int(rng.integers(-200 * l, 200 * l))
+        u = min(max(o + 128 * l, 0), 256 * l - 1)
+        t = u // l
+        got = (t ^ 0x80) - 256 if (t ^ 0x80) >= 128 else (t ^ 0x80)
+        assert got == max(-128, min(127, o // l))
+
+
+def test_folded_shift_exp2_equals_printed_form():
+    """((r >> 1) + s_inv) >> q == (r + 2 s_inv) >> (q + 1) for every r with r + 2 s_inv >= 0."""
+    rng = np.random.default_rng(2)
+    for _ in range(20000):
+        s_inv = int(rng.integers(1024, 1 << 18))
+        r = int(rng.integers(-2 * s_inv, s_inv // 8))
+        q = int(rng.integers(0, 29))
+        assert ((r >> 1) + s_inv) >> q == (r + 2 * s_inv) >> (q + 1)
+
+
+def test_scale_release_32bit_form():
+    """mul_hi(x << 2, alpha16 << 14) == floor(x * alpha16 / 2^16) for |x| < 2^26, alpha16 <= 2^16."""
+    rng = np.random.default_rng(3)
+    x = rng.integers(-(1 << 26) + 1, 1 << 26, size=20000).astype(object)
+    a = rng.integers(0, 65537, size=20000).astype(object)
+    a[:3] = [0, 65536, 1]
+    assert np.all(((x << 2) * (a << 14)) >> 32 == (x * a) >> 16)
+    assert max(abs(x << 2)) < (1 << 31) and max(a << 14) < (1 << 31)
