@@ -22,8 +22,10 @@
 //
 // The element-wise integer softmax is the binding resource (about ten VALU operations per score
 // against 256 MFMA operations and 1.3 HBM bytes), so the per-element path is written for the
-// full-rate 24-bit multiplier (v_mul_hi_i32_i24, v_mad_i32_i24) and packs its int8 result with an
-// SDWA byte write instead of separate shift/or operations.
+// full-rate 24-bit multiplier (v_mul_hi_i32_i24, v_mad_i32_i24), leaves its int8 result in the top
+// byte of a product and gathers four of them with v_perm_b32; where the constants allow it the
+// weights come from a table in LDS instead.  Inline assembly never reads a register written by an
+// MFMA: the compiler only places the wait states of the matrix pipeline for reads it can see.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -34,7 +36,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int kNegBig = -(1 << 30);   // stands for "excluded": far below any clamp point
+constexpr int kNegBig = -(1 << 30);   // stands for "excluded": far below any clamp point (so is
+                                      // anything a saturating add of INT32_MIN produces)
 constexpr int kMInit = -(1 << 21);    // initial running maximum (Algorithm 1)
 
 // ------------------------------------------------------------------ scalar building blocks
@@ -44,23 +47,6 @@ __device__ __forceinline__ int mulhi24(int a, int b) {
     const int a24 = (a << 8) >> 8, b24 = (b << 8) >> 8;
     return (int)(((long long)a24 * (long long)b24) >> 32);
 }
-// packed.byte[B] = (v >> sh) & 0xff, other bytes kept: the shift and the byte insert are one
-// SDWA instruction.  The caller guarantees (v >> sh) < 256.
-template <int B>
-__device__ __forceinline__ unsigned shr_into_byte(unsigned packed, unsigned sh, unsigned v) {
-    if (B == 0) return v >> sh;
-    if (B == 1)
-        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(sh), "v"(v));
-    if (B == 2)
-        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(sh), "v"(v));
-    if (B == 3)
-        asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
-            : "+v"(packed) : "v"(sh), "v"(v));
-    return packed;
-}
-
 // Exchange with the lane that holds the other half of the same query row.
 __device__ __forceinline__ int other_half(int v) { return __shfl_xor(v, 32, 64); }
 
@@ -120,13 +106,11 @@ __device__ __forceinline__ unsigned pack_byte(unsigned p0, unsigned p1, unsigned
 // ScaleRelease with alpha in 16 fractional bits: floor(x * alpha16 / 2^16) = ((x << 2) * (alpha16 << 14)) >> 32.
 // |x| < 2^26 and alpha16 <= 2^16 keep both factors inside 32 signed bits; the 32-bit multiply-high is
 // a full-rate instruction on gfx950.  alpha14 = alpha16 << 14 is formed once per row and tile.
-// The shift names alpha14 as an (unused) input so that it cannot be scheduled before alpha is known:
-// hoisted to the top of the tile it would keep a second copy of every accumulator alive.
-__device__ __forceinline__ int scale_release(int x, int alpha14) {
-    int x4;
-    asm("v_lshlrev_b32 %0, 2, %1 ; after %2" : "=v"(x4) : "v"(x), "v"(alpha14));
-    return __mulhi(x4, alpha14);
-}
+// The shift count is passed in as a register value derived from alpha (always 2) so that the shift
+// cannot be scheduled before alpha is known: hoisted to the top of the tile it would keep a
+// second copy of every accumulator alive.  No inline assembly here: the accumulators are MFMA
+// results and the compiler has to see every read of them to place the required wait states.
+__device__ __forceinline__ int scale_release(int x, int alpha14, int two) { return __mulhi(x << two, alpha14); }
 
 // R = ceil(2^(2L+8) / d) for d in (2^(L-1), 2^L], L = 16 or 20, in integer arithmetic only:
 // Newton's iteration for 1/d on 32-bit fixed point (32-bit multiply-high is full rate here),
@@ -203,14 +187,20 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const int col = cb + 4 * g + b;
+                    const bool beyond = !FULL && col >= n_valid;
                     int val = s[kb][4 * a4 + b];
-                    bool excl = col >= n_valid;
-                    if (BIAS && !excl) {
-                        const int bv = bias_row[col];
-                        excl = (bv == INT32_MIN);
-                        val += excl ? 0 : bv;
+                    if (BIAS) {
+                        // One saturating add does it all: the exclusion mark INT32_MIN drags the
+                        // score to the bottom of the range, below every clamp point, so it drops
+                        // out of the maximum and gets weight 0 without a compare and select.
+                        // (A builtin, not inline assembly: the compiler must see this read of an MFMA
+                        // result to insert the wait states the matrix pipeline needs.)
+                        const int bv = beyond ? INT32_MIN : bias_row[col];
+                        val = __builtin_elementwise_add_sat(val, bv);
+                    } else if (beyond) {
+                        val = kNegBig;
                     }
-                    s[kb][4 * a4 + b] = excl ? kNegBig : val;
+                    s[kb][4 * a4 + b] = val;
                 }
             }
         }
@@ -234,6 +224,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         const int a_hat = shift_exp2<KZ>(max(st.m, lo), m_new, m2, c);
         alpha14 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536) << 14;
     }
+    const int two = 2 + (alpha14 >> 31);   // alpha14 >= 0, so this is 2, but only known once alpha is
     v4i pk[KB];
     int rowsum = 0;
     if (XM == kExpTable) {
@@ -257,11 +248,11 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                 }
         __builtin_amdgcn_sched_barrier(0);
         if (!FIRST) {
-            st.l = scale_release(st.l, alpha14);
+            st.l = scale_release(st.l, alpha14, two);
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14);
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14, two);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -305,11 +296,11 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         if (FIRST) {
             st.l = rowsum;
         } else {
-            st.l = scale_release(st.l, alpha14) + rowsum;
+            st.l = scale_release(st.l, alpha14, two) + rowsum;
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14);
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14, two);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
