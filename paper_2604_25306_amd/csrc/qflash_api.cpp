@@ -212,11 +212,7 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
     const int64_t x0 = (41 * (int64_t)p->s_inv + ((int64_t)2 << p->x_shift) - 1) >> (p->x_shift + 1);
     if ((x0 << p->x_shift) * 2 > 57 * (int64_t)p->s_inv) return QFLASH_ERR_PARAM;  // > 28.5 octaves
     a.x_floor = (int)-x0;
-    qflash_plan_fwd(N, d, kv_tile, lds_limit, &a);
-    const int64_t units = (int64_t)B * H * a.n_qtiles;
-    if (units >= ((int64_t)1 << 30)) return QFLASH_ERR_SHAPE;
-    a.n_units = (int)units;
-    a.units_per_xcd = (a.n_units + 7) / 8;
+    if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
 
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }
@@ -233,7 +229,7 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
         const int n = (int)x_p + 1, n_padded = (n + 15) & ~15;
         std::lock_guard<std::mutex> lk(g_mu);
         if (ctx->use_table && ctx->tables && a.resident && n_padded <= kTableMaxBytes &&
-            qflash_table_fits(N, d, a.rows_per_wg, n_padded, lds_limit)) {
+            qflash_table_fits(a, d, n_padded, lds_limit)) {
             const int32_t key[5] = {p->x_shift, p->s_inv, p->exp_mul, p->p_mul, p->p_shift};
             int slot = -1;
             for (int i = 0; i < ctx->n_slots; ++i)

@@ -18,6 +18,8 @@ struct QflashKernelArgs {
     // work decomposition: one unit = (batch*head, query tile); XCD x owns units
     // [x*units_per_xcd, (x+1)*units_per_xcd)
     int rows_per_wg, n_qtiles, n_units, units_per_xcd;
+    int waves_per_head;      // wavefronts that serve one (batch, head) pair inside a workgroup
+    int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
     // look-up mode (resident kernel only): table of int8 weights, nullptr = compute them
     const uint8_t* lut;
@@ -28,12 +30,14 @@ struct QflashKernelArgs {
 // Enqueue the forward kernel for head size d (32|64), KV tile (64|128).  Returns a hipError_t value.
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 
-// Choose the kernel variant for a head of N rows and fill resident, rows_per_wg and n_qtiles.
+// Choose the kernel variant for BH heads of N rows and fill the work decomposition fields
+// (resident, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd).
+// Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
-int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);
+int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);
 
 // 1 if the resident kernel can also hold a weight table of table_bytes in LDS and copying it pays.
-int qflash_table_fits(int N, int d, int rows_per_wg, int table_bytes, int lds_limit);
+int qflash_table_fits(const QflashKernelArgs& args, int d, int table_bytes, int lds_limit);
 
 // Enqueue the kernel that fills a weight table of n entries (n_padded bytes) for args' constants.
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashKernelArgs& args, void* stream);

@@ -415,33 +415,42 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int N = a.N;
     const int npad = (N + 31) & ~31;
     const int VROW = npad + 16;
-    // LDS: [weight table, lut_bytes (table mode only)] [K: npad x KROW] [V^T: D x VROW].  The table
-    // sits at offset 0 so that its index is the LDS address.
+    // A workgroup serves heads_per_wg consecutive (batch, head) pairs when one pair needs only a
+    // few wavefronts (windowed attention): wavefront w belongs to pair w / waves_per_head.  Each
+    // pair's K and V^T are staged by its own wavefronts; the weight table is shared.
+    // LDS: [weight table, lut_bytes (table mode only)] then per pair [K: npad x KROW] [V^T: D x VROW].
+    // The table sits at offset 0 so that its index is the LDS address.
     const int tbytes = XM == kExpTable ? a.lut_bytes : 0;
     const uint8_t* sT = (const uint8_t*)smem;
-    int8_t* sK = smem + tbytes;
-    int8_t* sV = sK + (size_t)npad * KROW;
 
     const int wg = blockIdx.x;
     const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
     if (unit >= a.n_units) return;
-    const int qt = unit % a.n_qtiles;
-    const int bh = unit / a.n_qtiles;
 
-    const int tid = threadIdx.x, nthr = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int wg_tid = threadIdx.x, wg_nthr = blockDim.x;
+    const int lane = wg_tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(wg_tid >> 6);   // uniform: index math on the scalar unit
     const int g = lane >> 5, li = lane & 31;
-    const int row0 = qt * a.rows_per_wg + wave * 32;
+    const int sub = a.heads_per_wg > 1 ? wave / a.waves_per_head : 0;   // which pair of this workgroup
+    const int tid = wg_tid - sub * a.waves_per_head * 64;    // thread index within the pair
+    const int nthr = a.waves_per_head * 64;
+    const int qt = a.heads_per_wg > 1 ? 0 : unit % a.n_qtiles;
+    const int bh = a.heads_per_wg > 1 ? unit * a.heads_per_wg + sub : unit / a.n_qtiles;
+    const bool pair_valid = bh < a.B * a.H;
+    const int row0 = qt * a.rows_per_wg + (wave - sub * a.waves_per_head) * 32;
     const int i = row0 + li;
 
-    const size_t head_off = (size_t)bh * N * D;
+    int8_t* sK = smem + tbytes + (size_t)sub * ((size_t)npad * KROW + (size_t)D * VROW);
+    int8_t* sV = sK + (size_t)npad * KROW;
+
+    const size_t head_off = (size_t)(pair_valid ? bh : 0) * N * D;
     const int8_t* Qh = a.Q + head_off;
     const int8_t* Kh = a.K + head_off;
     const int8_t* Vh = a.V + head_off;
 
     // ---- stage the weight table (L2-resident, shared by every workgroup of the launch)
     if (XM == kExpTable)
-        for (int ch = tid; ch < tbytes / 16; ch += nthr) *(v4i*)(smem + 16 * ch) = *(const v4i*)(a.lut + 16 * ch);
+        for (int ch = wg_tid; ch < tbytes / 16; ch += wg_nthr) *(v4i*)(smem + 16 * ch) = *(const v4i*)(a.lut + 16 * ch);
     // ---- stage the whole K (row-major) and V^T (permuted columns) of this head
     for (int ch = tid; ch < npad * (D / 16); ch += nthr) {
         const int r = ch / (D / 16), c16 = ch % (D / 16);
@@ -460,7 +469,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
         if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
     }
     __syncthreads();
-    if (row0 >= N) return;            // wavefront without query rows (after the only barrier)
+    if (row0 >= N || !pair_valid) return;   // wavefront without query rows (after the only barrier)
 
     const int32_t* bias_row = nullptr;
     if (BIAS) {
@@ -639,37 +648,54 @@ int launch_dbc(const QflashKernelArgs& a, bool resident, size_t lds, int lds_lim
 
 }  // namespace
 
-// LDS bytes of the resident kernel for a head of N rows (K, V^T and the weight table), or 0 if
-// they do not fit.
-static size_t resident_lds_bytes(int N, int d, int table_bytes, int lds_limit) {
+// LDS bytes of the resident kernel: K and V^T of `heads` heads of N rows and the weight table;
+// 0 if they do not fit.
+static size_t resident_lds_bytes(int N, int d, int heads, int table_bytes, int lds_limit) {
     const size_t npad = (size_t)((N + 31) & ~31);
-    const size_t bytes = npad * (size_t)(d + 16) + (size_t)d * (npad + 16) + (size_t)table_bytes;
+    const size_t bytes = (size_t)heads * (npad * (size_t)(d + 16) + (size_t)d * (npad + 16)) + (size_t)table_bytes;
     return bytes <= (size_t)lds_limit ? bytes : 0;
 }
 
-int qflash_plan_fwd(int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* a) {
+int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* a) {
     (void)kv_tile;
-    a->resident = resident_lds_bytes(N, d, 0, lds_limit) != 0;
+    a->resident = resident_lds_bytes(N, d, 1, 0, lds_limit) != 0;
+    a->heads_per_wg = 1;
     if (a->resident) {
         const int nblk = (N + 31) / 32;
         const int max_waves = N <= 256 ? resident_max_waves<true>() : resident_max_waves<false>();
         const int tiles = (nblk + max_waves - 1) / max_waves;
         const int waves = (nblk + tiles - 1) / tiles;       // balanced
         a->rows_per_wg = 32 * waves;
+        a->waves_per_head = waves;
+        // Short sequences (windowed attention): several (batch, head) pairs per workgroup, so that
+        // a workgroup is 8 wavefronts and a weight table is staged once for all of them.
+        if (tiles == 1 && waves <= 4) {
+            int hp = resident_max_waves<true>() / waves;
+            if (hp > BH) hp = BH;
+            while (hp > 1 && resident_lds_bytes(N, d, hp, 0, lds_limit / 4) == 0) --hp;
+            a->heads_per_wg = hp;
+        }
     } else {
         a->rows_per_wg = kStreamRows;
+        a->waves_per_head = kStreamWaves;
     }
     a->n_qtiles = (N + a->rows_per_wg - 1) / a->rows_per_wg;
+    const long long units = a->heads_per_wg > 1 ? ((long long)BH + a->heads_per_wg - 1) / a->heads_per_wg
+                                                : (long long)BH * a->n_qtiles;
+    if (units >= (1ll << 30)) return -1;
+    a->n_units = (int)units;
+    a->units_per_xcd = (a->n_units + 7) / 8;
     return 0;
 }
 
-int qflash_table_fits(int N, int d, int rows_per_wg, int table_bytes, int lds_limit) {
-    // Every workgroup copies the table into its LDS: worth it only if the workgroup then reads
-    // at least about one weight per table byte.
-    if ((long long)rows_per_wg * N < (long long)table_bytes) return 0;
+int qflash_table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds_limit) {
+    // Every workgroup copies the table from L2 into its LDS: worth it only while that stays below
+    // the bytes of Q, K, V, O the workgroup moves anyway.
+    const long long io = 4ll * a.heads_per_wg * a.N * d;
+    if (io < (long long)table_bytes) return 0;
     // keep two workgroups per CU when the sequence is short enough for that to matter
-    const int budget = N <= 256 ? lds_limit / 2 : lds_limit;
-    return resident_lds_bytes(N, d, table_bytes, budget) != 0;
+    const int budget = a.N <= 256 ? lds_limit / 2 : lds_limit;
+    return resident_lds_bytes(a.N, d, a.heads_per_wg, table_bytes, budget) != 0;
 }
 
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashKernelArgs& a, void* stream) {
@@ -680,9 +706,9 @@ int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const 
 
 int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.lut ? a.lut_bytes : 0, lds_limit) : 0;
+    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.lut ? a.lut_bytes : 0, lds_limit) : 0;
     if (a.resident && lds == 0) return (int)hipErrorInvalidValue;
-    const int threads = a.resident ? 2 * a.rows_per_wg : kStreamThreads;
+    const int threads = a.resident ? 64 * a.waves_per_head * a.heads_per_wg : kStreamThreads;
     if (d == 64 && kv_tile == 64) return launch_dbc<64, 64>(a, a.resident, lds, lds_limit, threads, st);
     if (d == 64 && kv_tile == 128) return launch_dbc<64, 128>(a, a.resident, lds, lds_limit, threads, st);
     if (d == 32 && kv_tile == 64) return launch_dbc<32, 64>(a, a.resident, lds, lds_limit, threads, st);
