@@ -15,9 +15,10 @@
 //   the contraction does not change a single bit of the result.
 //
 // Two kernels share the per-tile code:
-//   resident  one workgroup = one (batch, head) and up to 16 wavefronts of 32 query rows; the
-//             whole K and V^T of the head are staged in LDS once (N up to about 1100), after
-//             which the wavefronts run independently, with no barrier in the KV loop.
+//   resident  one workgroup = one (batch, head) pair and up to 8 (N <= 256) or 12 wavefronts of
+//             32 query rows, or several short pairs (windowed attention) side by side; the whole
+//             K and V^T of each pair are staged in LDS once (N up to about 1100), after which
+//             the wavefronts run independently, with no barrier in the KV loop.
 //   stream    one workgroup = 128 query rows; KV tiles are staged per iteration (any N).
 //
 // The element-wise integer softmax is the binding resource (about ten VALU operations per score
