@@ -21,6 +21,7 @@ struct QflashKernelArgs {
     int waves_per_head;      // wavefronts that serve one (batch, head) pair inside a workgroup
     int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
+    int pipelined;           // resident only: K/V tiles are staged one ahead of their use
     // look-up mode (resident kernel only): table of int8 weights, nullptr = compute them
     const uint8_t* lut;
     int lut_bytes;           // bytes staged into LDS (multiple of 16)

@@ -48,8 +48,15 @@ __device__ __forceinline__ int mulhi24(int a, int b) {
     const int a24 = (a << 8) >> 8, b24 = (b << 8) >> 8;
     return (int)(((long long)a24 * (long long)b24) >> 32);
 }
-// Exchange with the lane that holds the other half of the same query row.
-__device__ __forceinline__ int other_half(int v) { return __shfl_xor(v, 32, 64); }
+// The two lanes l and l ^ 32 hold the halves of one query row.  One cross-lane swap in the vector
+// ALU (no round trip through the LDS crossbar) hands each of them both values: the swap exchanges
+// the upper half of its first operand with the lower half of the second, so with both operands
+// equal to v every lane ends up with {own, partner's} in some order -- enough for max and sum.
+struct HalfPair { int x, y; };
+__device__ __forceinline__ HalfPair both_halves(int v) {
+    const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return HalfPair{(int)sw[0], (int)sw[1]};
+}
 
 // Loop-invariant constants of Algorithm 2 / Eq. 10 kept in registers.
 struct ExpConst {
@@ -104,14 +111,37 @@ __device__ __forceinline__ unsigned pack_byte(unsigned p0, unsigned p1, unsigned
     return __builtin_amdgcn_perm(p3, w, (h << 24) | 0x020100u);
 }
 
-// ScaleRelease with alpha in 16 fractional bits: floor(x * alpha16 / 2^16) = ((x << 2) * (alpha16 << 14)) >> 32.
-// |x| < 2^26 and alpha16 <= 2^16 keep both factors inside 32 signed bits; the 32-bit multiply-high is
-// a full-rate instruction on gfx950.  alpha14 = alpha16 << 14 is formed once per row and tile.
-// The shift count is passed in as a register value derived from alpha (always 2) so that the shift
-// cannot be scheduled before alpha is known: hoisted to the top of the tile it would keep a
-// second copy of every accumulator alive.  No inline assembly here: the accumulators are MFMA
-// results and the compiler has to see every read of them to place the required wait states.
-__device__ __forceinline__ int scale_release(int x, int alpha14, int two) { return __mulhi(x << two, alpha14); }
+// ScaleRelease with alpha in 16 fractional bits, floor(x * alpha16 / 2^16), 0 <= alpha16 <= 2^16.
+//
+// Numerator accumulators are kept with their sign bit flipped, y = x + 2^31 read as unsigned
+// (the MFMA adds products modulo 2^32, so the offset rides along).  With A = alpha16 << 16:
+//   mul_hi_u32(y, A) = floor((x A + 2^31 A) / 2^32) = floor(x alpha16 / 2^16) + A/2      (A is even)
+// so the rescaled accumulator, again offset by 2^31, is mul_hi_u32(y, A) + (2^31 - A/2): one
+// multiply-high and one add, no shift.  alpha16 = 2^16 (identity) does not fit A; there
+// A = 2^32 - 1 gives mul_hi_u32(y, A) = y - 1 for every 1 <= y < 2^32, and the addend is 1.
+// (|x| < 2^31 - 1 always: the accumulators stay below 2^26.)
+struct ReleaseConst {
+    unsigned A, C;       // accumulator: y <- mul_hi_u32(y, A) + C
+    int alpha14;         // alpha16 << 14, for the (unbiased, non-negative) denominator
+};
+__device__ __forceinline__ ReleaseConst make_release(unsigned alpha16) {
+    ReleaseConst r;
+    const unsigned one = alpha16 >> 16;   // 1 only for the identity
+    r.A = (alpha16 << 16) - one;
+    r.C = 0x80000000u - (alpha16 << 15) + one;
+    r.alpha14 = (int)(alpha16 << 14);
+    return r;
+}
+__device__ __forceinline__ int release_acc(int y, const ReleaseConst& r) { return (int)(__umulhi((unsigned)y, r.A) + r.C); }
+// Denominator: 0 <= l < 2^20, floor(l * alpha16 / 2^16) = ((l << 2) * (alpha16 << 14)) >> 32.
+__device__ __forceinline__ int release_l(int l, const ReleaseConst& r) { return __mulhi(l << 2, r.alpha14); }
+
+constexpr int kAccBias = (int)0x80000000u;   // offset carried by numerator accumulators and biased scores
+
+// One byte of the weight table.  The table is the first thing in the workgroup's LDS (the resident
+// kernel has no other LDS object, so its dynamic LDS starts at address 0): the index is the address.
+typedef const __attribute__((address_space(3))) uint8_t lds_u8;
+__device__ __forceinline__ int table_weight(unsigned idx) { return (int)*(lds_u8*)(size_t)idx; }
 
 // R = ceil(2^(2L+8) / d) for d in (2^(L-1), 2^L], L = 16 or 20, in integer arithmetic only:
 // Newton's iteration for 1/d on 32-bit fixed point (32-bit multiply-high is full rate here),
@@ -150,15 +180,30 @@ struct RowState {
 // XM selects how the int8 weight of a score is obtained: kExpShift (Algorithm 2 + Eq. 10 in the
 // ALUs, any x_shift), kExpShift0 (the same, x_shift == 0) or kExpTable (one LDS look-up in a table
 // of the same function, see qflash_build_table).
+//
+// Offsets.  Numerator accumulators always carry +2^31 (see ReleaseConst).  In table mode without
+// bias the scores can carry it too (SB): the first MFMA of a score block starts from a
+// register block `zb` full of 0x80000000 instead of zeros, which costs nothing, and then
+//   table index = max(0, s - m + x_p) = (s + 2^31) -sat- (m + 2^31 - x_p)
+// is a single unsigned saturating subtraction per score; the maximum is taken unsigned and
+// RowState::m holds m + 2^31.  Algorithm 2 for alpha only sees differences, which are unchanged.
 enum { kExpShift = 0, kExpShift0 = 1, kExpTable = 2 };
 
-template <int D, int BC, bool BIAS, int XM, bool FULL, bool FIRST>
+// Biased scores need 16 more registers; they are used where the kernel variant has them to spare.
+template <int D, int BC, bool BIAS, bool NARROW, int XM>
+constexpr bool score_biased() { return XM == kExpTable && !BIAS && D == 64 && (BC == 64 || !NARROW); }
+
+template <bool SB>
+__device__ __forceinline__ int smax(int a, int b) { return SB ? (int)max((unsigned)a, (unsigned)b) : max(a, b); }
+
+template <int D, int BC, bool BIAS, int XM, bool SB, bool FULL, bool FIRST>
 __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
-                                            const int8_t* sV, int VROW, int n_valid_rt, const uint8_t* sT, int x_p,
+                                            const int8_t* sV, int VROW, int n_valid_rt, int x_p,
                                             const int32_t* bias_row /* + c0 */, const ExpConst& c,
-                                            int a_mul, int li, int g) {
+                                            int a_mul, int li, int g, const v16i& zb) {
     constexpr int KSTEPS = D / 32, TB = D / 32, KB = BC / 32;
     constexpr bool KZ = XM == kExpShift0;
+    static_assert(!SB || (XM == kExpTable && !BIAS), "biased scores: table mode without bias only");
     // FULL: the tile has all BC kv rows, every "is this group inside the sequence" test below is
     // true at compile time and the tile is one straight line of code.
     const int n_valid = FULL ? BC : n_valid_rt;
@@ -168,7 +213,8 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
     for (int kb = 0; kb < KB; ++kb) {
         if (32 * kb < n_valid) {
             const v4i ka0 = *(const v4i*)(sK + (32 * kb + li) * KROW + 16 * g);
-            s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], v16i{0}, 0, 0, 0);
+            s[kb] = SB ? __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], zb, 0, 0, 0)
+                       : __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], v16i{0}, 0, 0, 0);
 #pragma unroll
             for (int ks = 1; ks < KSTEPS; ++ks) {
                 const v4i ka = *(const v4i*)(sK + (32 * kb + li) * KROW + 32 * ks + 16 * g);
@@ -199,7 +245,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                         const int bv = beyond ? INT32_MIN : bias_row[col];
                         val = __builtin_elementwise_add_sat(val, bv);
                     } else if (beyond) {
-                        val = kNegBig;
+                        val = SB ? 0 : kNegBig;   // below every real score in either representation
                     }
                     s[kb][4 * a4 + b] = val;
                 }
@@ -212,26 +258,29 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4)
             if (32 * kb + 8 * a4 < n_valid) {
-                m_new = max(m_new, max(s[kb][4 * a4], s[kb][4 * a4 + 1]));
-                m_new = max(m_new, max(s[kb][4 * a4 + 2], s[kb][4 * a4 + 3]));
+                m_new = smax<SB>(m_new, smax<SB>(s[kb][4 * a4], s[kb][4 * a4 + 1]));
+                m_new = smax<SB>(m_new, smax<SB>(s[kb][4 * a4 + 2], s[kb][4 * a4 + 3]));
             }
-    m_new = max(m_new, other_half(m_new));
+    {
+        const HalfPair hp = both_halves(m_new);
+        m_new = smax<SB>(hp.x, hp.y);
+    }
     const int lo = m_new + c.x_floor;
     const int m2 = m_new - 2 * c.s_inv;
-    const int x_p_v = XM == kExpTable ? to_vgpr(x_p) : 0;
-    // ---- step 4: max-offset factor alpha, brought to 16 fractional bits (kept as alpha16 << 14)
-    int alpha14 = 0;
+    // ---- step 4: max-offset factor alpha, brought to 16 fractional bits
+    ReleaseConst rel;
     if (!FIRST) {
-        const int a_hat = shift_exp2<KZ>(max(st.m, lo), m_new, m2, c);
-        alpha14 = min((int)(((unsigned)a_hat * (unsigned)a_mul) >> 14), 65536) << 14;
+        const int a_hat = shift_exp2<KZ>(smax<SB>(st.m, lo), m_new, m2, c);
+        rel = make_release(min(((unsigned)a_hat * (unsigned)a_mul) >> 14, 65536u));
     }
-    const int two = 2 + (alpha14 >> 31);   // alpha14 >= 0, so this is 2, but only known once alpha is
     v4i pk[KB];
     int rowsum = 0;
     if (XM == kExpTable) {
         // ---- steps 5,6 by table: issue every look-up of the tile, rescale the accumulators while
         //      the LDS answers, then pack.  Index 0 of the table is the weight 0 of everything at
         //      or below -x_p (excluded scores included).
+        const unsigned x_p_v = (unsigned)to_vgpr(x_p);
+        const unsigned edge = (unsigned)m_new - x_p_v;       // score_biased: m + 2^31 - x_p > 0
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -239,21 +288,21 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                 if (32 * kb + 8 * a4 < n_valid) {
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
-                        // index = max(x_p - (m - s), 0): two fast-class subtractions, the second one
-                        // saturating at 0 (m - s >= 0; excluded scores give a huge difference)
-                        const unsigned dist = (unsigned)(m_new - s[kb][4 * a4 + b]);
-                        unsigned idx;
-                        asm("v_sub_u32_e64 %0, %1, %2 clamp" : "=v"(idx) : "v"(x_p_v), "v"(dist));
-                        s[kb][4 * a4 + b] = sT[idx];
+                        // Saturating subtractions are fast-class instructions; as builtins, because
+                        // they read MFMA results.
+                        const unsigned sv = (unsigned)s[kb][4 * a4 + b];
+                        const unsigned idx = SB ? __builtin_elementwise_sub_sat(sv, edge)
+                                                : __builtin_elementwise_sub_sat(x_p_v, (unsigned)m_new - sv);
+                        s[kb][4 * a4 + b] = table_weight(idx);
                     }
                 }
         __builtin_amdgcn_sched_barrier(0);
         if (!FIRST) {
-            st.l = scale_release(st.l, alpha14, two);
+            st.l = release_l(st.l, rel);
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14, two);
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = release_acc(st.acc[t][v], rel);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -262,13 +311,16 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 #pragma unroll
             for (int a4 = 0; a4 < 4; ++a4)
                 if (32 * kb + 8 * a4 < n_valid) {
-                    const unsigned w = (unsigned)s[kb][4 * a4] | ((unsigned)s[kb][4 * a4 + 1] << 8) |
-                                       ((unsigned)s[kb][4 * a4 + 2] << 16) | ((unsigned)s[kb][4 * a4 + 3] << 24);
+                    const unsigned w = pack_byte<0>((unsigned)s[kb][4 * a4], (unsigned)s[kb][4 * a4 + 1],
+                                                    (unsigned)s[kb][4 * a4 + 2], (unsigned)s[kb][4 * a4 + 3]);
                     pk[kb][a4] = (int)w;
                     rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);   // step 7
                 }
         }
-        rowsum += other_half(rowsum);
+        {
+            const HalfPair hp = both_halves(rowsum);
+            rowsum = hp.x + hp.y;
+        }
         st.l += rowsum;                                                                    // step 9
     } else {
         // ---- steps 5,6,7: score intensity, requantisation to int8 (Eq. 10), row sum
@@ -289,7 +341,10 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                     rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
                 }
         }
-        rowsum += other_half(rowsum);
+        {
+            const HalfPair hp = both_halves(rowsum);
+            rowsum = hp.x + hp.y;
+        }
         // Keep the phases apart: letting the scheduler overlap the rescale below with the
         // element-wise work above only lengthens live ranges (spills) without gaining issue slots.
         __builtin_amdgcn_sched_barrier(0);
@@ -297,22 +352,23 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         if (FIRST) {
             st.l = rowsum;
         } else {
-            st.l = scale_release(st.l, alpha14, two) + rowsum;
+            st.l = release_l(st.l, rel) + rowsum;
 #pragma unroll
             for (int t = 0; t < TB; ++t)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) st.acc[t][v] = scale_release(st.acc[t][v], alpha14, two);
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = release_acc(st.acc[t][v], rel);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // ---- step 8: O^T += V_j^T P^T
+    // ---- step 8: O^T += V_j^T P^T (the first tile starts the accumulators at their offset 2^31)
 #pragma unroll
     for (int t = 0; t < TB; ++t)
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
             if (32 * kb < n_valid) {
                 const v4i va = *(const v4i*)(sV + (32 * t + li) * VROW + 32 * kb + 16 * g);
-                st.acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], st.acc[t], 0, 0, 0);
+                st.acc[t] = (FIRST && kb == 0) ? __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], zb, 0, 0, 0)
+                                               : __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], st.acc[t], 0, 0, 0);
             }
     st.m = m_new;
 }
@@ -334,9 +390,14 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
     const int z = L - (32 - __clz((int)(dsafe - 1)));          // dsafe << z in (2^(L-1), 2^L]
     const unsigned dn = dsafe << z;
     const unsigned R = recip_ceil<L>(dn);
+    // The accumulators carry +2^31 (ReleaseConst).  It vanishes in the left shift below, which is
+    // by z + rs >= 1 bits: l <= 127 N < 2^(L-1) for the N each L is used with, so z >= 1 when
+    // rs = 0, and rs = 1 otherwise.
     const int bias_z = (int)((128u * dsafe + (round_nearest ? (unsigned)st.l : 0u)) << z);
     const int u_max = (int)(256u * dn) - 1;
     const int zz = z + rs;
+    // word[j]: features 8 j + 4 g + (0..3) of this lane's row, j = 4 t + a4
+    unsigned word[4 * TB];
 #pragma unroll
     for (int t = 0; t < TB; ++t)
 #pragma unroll
@@ -348,10 +409,25 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
                 u = min(max(u, 0), u_max);
                 hi[b] = __umulhi((unsigned)u, R);
             }
-            unsigned word = pack_byte<(2 * L + 8 - 32) / 8>(hi[0], hi[1], hi[2], hi[3]) ^ 0x80808080u;
-            if (empty) word = 0;
-            *(unsigned*)(Orow + 32 * t + 8 * a4 + 4 * g) = word;
+            const unsigned w = pack_byte<(2 * L + 8 - 32) / 8>(hi[0], hi[1], hi[2], hi[3]) ^ 0x80808080u;
+            word[4 * t + a4] = empty ? 0u : w;
         }
+    // The two lanes of a row hold alternate dwords of it.  Swapping the second half of the row of
+    // lane g = 0 against the first half of lane g = 1 (one cross-lane swap per dword) leaves each
+    // lane with one contiguous half of the row, written with 16-byte stores: dword-sized stores
+    // scattered over 32 rows per instruction cost more time than the whole computation.
+    constexpr int HALF = 2 * TB;   // dwords a lane owns after the swap (as many as before it)
+    unsigned ev[HALF], od[HALF];   // even / odd dwords of this lane's half
+#pragma unroll
+    for (int j = 0; j < HALF; ++j) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(word[j], word[HALF + j], false, false);
+        ev[j] = sw[0];
+        od[j] = sw[1];
+    }
+    int8_t* dst = Orow + g * (D / 2);
+#pragma unroll
+    for (int q = 0; q < HALF / 2; ++q)
+        *(v4i*)(dst + 16 * q) = v4i{(int)ev[2 * q], (int)od[2 * q], (int)ev[2 * q + 1], (int)od[2 * q + 1]};
 }
 
 __device__ __forceinline__ ExpConst make_exp_const(const QflashKernelArgs& a) {
@@ -378,15 +454,17 @@ __device__ __forceinline__ void transpose4x4(const unsigned r[4], unsigned o[4])
 
 // V rows [r0, r0+4) x features [8*t8, 8*t8+8) -> V^T in LDS, kv columns in result-layout order.
 // lds_col_blk = LDS column where the 32-row kv block of r0 starts; r_in_blk = r0 % 32 (multiple of 4).
+// Split into the global loads and the transposing LDS writes so that the loads of the next KV
+// tile can be in flight while the current one is being processed.
 typedef int v2i __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void stage_v_4x8(const int8_t* Vh, int D, int N, int r0, int t8, int8_t* sV, int VROW,
-                                            int lds_col_blk, int r_in_blk) {
-    v2i rw[4];
+__device__ __forceinline__ void load_v_4x8(const int8_t* Vh, int D, int N, int r0, int t8, v2i rw[4]) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         rw[b] = v2i{0, 0};
         if (r0 + b < N) rw[b] = *(const v2i*)(Vh + (size_t)(r0 + b) * D + 8 * t8);
     }
+}
+__device__ __forceinline__ void store_v_4x8(const v2i rw[4], int t8, int8_t* sV, int VROW, int lds_col_blk, int r_in_blk) {
     // kv row 8*a4 + 4*g2 + b of a block  ->  slot 16*g2 + 4*a4 + b
     const int pos = lds_col_blk + 16 * ((r_in_blk >> 2) & 1) + 4 * (r_in_blk >> 3);
 #pragma unroll
@@ -397,6 +475,12 @@ __device__ __forceinline__ void stage_v_4x8(const int8_t* Vh, int D, int N, int 
 #pragma unroll
         for (int f = 0; f < 4; ++f) *(unsigned*)(sV + (8 * t8 + 4 * w + f) * VROW + pos) = o[f];
     }
+}
+__device__ __forceinline__ void stage_v_4x8(const int8_t* Vh, int D, int N, int r0, int t8, int8_t* sV, int VROW,
+                                            int lds_col_blk, int r_in_blk) {
+    v2i rw[4];
+    load_v_4x8(Vh, D, N, r0, t8, rw);
+    store_v_4x8(rw, t8, sV, VROW, lds_col_blk, r_in_blk);
 }
 
 // ------------------------------------------------------------------------ resident kernel
@@ -422,7 +506,6 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // LDS: [weight table, lut_bytes (table mode only)] then per pair [K: npad x KROW] [V^T: D x VROW].
     // The table sits at offset 0 so that its index is the LDS address.
     const int tbytes = XM == kExpTable ? a.lut_bytes : 0;
-    const uint8_t* sT = (const uint8_t*)smem;
 
     const int wg = blockIdx.x;
     const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
@@ -449,28 +532,123 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int8_t* Kh = a.K + head_off;
     const int8_t* Vh = a.V + head_off;
 
-    // ---- stage the weight table (L2-resident, shared by every workgroup of the launch)
-    if (XM == kExpTable)
-        for (int ch = wg_tid; ch < tbytes / 16; ch += wg_nthr) *(v4i*)(smem + 16 * ch) = *(const v4i*)(a.lut + 16 * ch);
-    // ---- stage the whole K (row-major) and V^T (permuted columns) of this head
-    for (int ch = tid; ch < npad * (D / 16); ch += nthr) {
-        const int r = ch / (D / 16), c16 = ch % (D / 16);
-        v4i val = {0, 0, 0, 0};
-        if (r < N) val = *(const v4i*)(Kh + (size_t)r * D + 16 * c16);
-        *(v4i*)(sK + r * KROW + 16 * c16) = val;
+    // ---- K (row-major) and V^T (permuted columns) of this pair go to LDS either all at once, or
+    //      (a.pipelined) one KV tile at a time: the global loads of tile j+1 are issued before tile
+    //      j is processed and written to LDS after it, so that memory latency and the first pass
+    //      over HBM overlap with the arithmetic instead of preceding it.  Every tile has its own
+    //      LDS region, so one barrier per tile (publishing it) is all the synchronisation needed.
+    // (compiled in only where the kernel variant has the registers for the tile in flight)
+    constexpr bool PIPE_OK = D == 64 && (BC == 64 || !NARROW);
+    const bool pipelined = PIPE_OK && a.pipelined != 0;
+    const int n_tiles = (N + BC - 1) / BC;
+    // One staging item per thread and tile: 32 bytes of a K row, or a 4-row x 8-feature block of
+    // V; either way four 8-byte loads, issued without any branch around them (rows beyond the
+    // sequence read row N-1 and are zeroed when written to LDS): straight-line loads are what
+    // lets the compiler count exactly which of them a later wait has to cover.
+    v2i pf[4], pf0[4];   // tile in flight; tile 0 (prologue only)
+    auto load_tile = [&](int j, v2i* pf) {
+        const int c0 = j * BC;
+        const int rows_t = min(BC, npad - c0);
+        const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
+        if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {   // whole wavefronts, nK + nV is a multiple of 64
+            const bool is_k = tid < nK;
+            const int iv = tid - nK;
+            const int8_t* base = is_k ? Kh : Vh;
+            const int row = c0 + (is_k ? tid / (D / 32) : 4 * (iv / (D / 8)));
+            const int col = is_k ? 32 * (tid % (D / 32)) : 8 * (iv % (D / 8));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int rb = min(is_k ? row : row + b, N - 1);
+                pf[b] = *(const v2i*)(base + (size_t)rb * D + col + (is_k ? 8 * b : 0));
+            }
+        }
+    };
+    auto write_tile = [&](int j, const v2i* pf) {
+        const int c0 = j * BC;
+        const int rows_t = min(BC, npad - c0);
+        const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
+        if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {
+            if (__builtin_amdgcn_readfirstlane(tid) < nK) {
+                const int r = c0 + tid / (D / 32), h = tid % (D / 32);
+                const bool ok = r < N;
+                v4i lo = {pf[0][0], pf[0][1], pf[1][0], pf[1][1]}, hi = {pf[2][0], pf[2][1], pf[3][0], pf[3][1]};
+                if (!ok) lo = hi = v4i{0, 0, 0, 0};
+                *(v4i*)(sK + r * KROW + 32 * h) = lo;
+                *(v4i*)(sK + r * KROW + 32 * h + 16) = hi;
+            } else {
+                const int iv = tid - nK;
+                const int r0 = c0 + 4 * (iv / (D / 8));
+                v2i rw[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) rw[b] = r0 + b < N ? pf[b] : v2i{0, 0};
+                store_v_4x8(rw, iv % (D / 8), sV, VROW, r0 & ~31, r0 & 31);
+            }
+        }
+    };
+    // Order of the prologue: the loads with the longest way to go first (K/V tile 0 from HBM), then
+    // the query rows, then the table (L2); all of them are in flight together and the first wait
+    // covers them all.
+    if (pipelined) {
+        load_tile(0, pf0);
+        if (n_tiles > 1) load_tile(1, pf);
     }
-    for (int sb = tid; sb < (npad / 4) * (D / 8); sb += nthr) {
-        const int t8 = sb % (D / 8), r0 = 4 * (sb / (D / 8));
-        stage_v_4x8(Vh, D, N, r0, t8, sV, VROW, r0 & ~31, r0 & 31);
-    }
+    // ---- this lane's query row.  Lanes beyond the sequence read the last row instead (their
+    //      results are never stored and rows do not interact), which keeps the loads free of branches.
     v4i qreg[KSTEPS];
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) {
-        qreg[s] = v4i{0, 0, 0, 0};
-        if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
+    for (int s = 0; s < KSTEPS; ++s) qreg[s] = *(const v4i*)(Qh + (size_t)min(i, N - 1) * D + 32 * s + 16 * g);
+    // ---- loop-invariant registers, set up before any K/V tile is in flight
+    const ExpConst c = make_exp_const(a);
+    constexpr bool SB = score_biased<D, BC, BIAS, NARROW, XM>();
+    // Block of 0x80000000 that starts the accumulators (and, with biased scores, every score
+    // block) at their offset.  With biased scores it is used in every tile: made opaque so that it
+    // stays in 16 registers instead of being rebuilt by 16 moves per use.
+    v16i zb;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) zb[v] = kAccBias;
+    if (SB) asm volatile("" : "+v"(zb));
+    RowState<D> st;
+    st.l = 0;
+    st.m = SB ? (int)((unsigned)kMInit + (unsigned)kAccBias) : kMInit;
+
+    // ---- stage the weight table (L2-resident, shared by every workgroup of the launch): four
+    //      16-byte pieces per thread in flight at a time
+    if (XM == kExpTable) {
+        const int nch = tbytes / 16;
+        for (int ch0 = wg_tid; ch0 < nch; ch0 += 4 * wg_nthr) {
+            v4i t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (ch0 + u * wg_nthr < nch) t[u] = *(const v4i*)(a.lut + 16 * (ch0 + u * wg_nthr));
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (ch0 + u * wg_nthr < nch) *(v4i*)(smem + 16 * (ch0 + u * wg_nthr)) = t[u];
+        }
     }
+    if (!pipelined) {
+        for (int ch = tid; ch < npad * (D / 16); ch += nthr) {
+            const int r = ch / (D / 16), c16 = ch % (D / 16);
+            v4i val = {0, 0, 0, 0};
+            if (r < N) val = *(const v4i*)(Kh + (size_t)r * D + 16 * c16);
+            *(v4i*)(sK + r * KROW + 16 * c16) = val;
+        }
+        for (int sb = tid; sb < (npad / 4) * (D / 8); sb += nthr) {
+            const int t8 = sb % (D / 8), r0 = 4 * (sb / (D / 8));
+            stage_v_4x8(Vh, D, N, r0, t8, sV, VROW, r0 & ~31, r0 & 31);
+        }
+    }
+    // Touch the query registers here, on every path, where the loads so far have to be waited for
+    // anyway.  Otherwise their first use sits inside the tile code, which wavefronts without rows
+    // skip, and the compiler has to assume at every later tile that the query load may still be
+    // pending; loads complete in order, so that wait would cover the K/V tile in flight as well.
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) asm volatile("" : "+v"(qreg[s]));
+    if (pipelined) write_tile(0, pf0);
     __syncthreads();
-    if (row0 >= N || !pair_valid) return;   // wavefront without query rows (after the only barrier)
+    // A wavefront without query rows leaves after the only barrier, unless it still has tiles to
+    // stage for the others.
+    const bool active = row0 < N && pair_valid;
+    if (!active && !pipelined) return;
 
     const int32_t* bias_row = nullptr;
     if (BIAS) {
@@ -478,28 +656,41 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
         bias_row = a.bias + ((size_t)(b % a.bias_B) * a.bias_H + (size_t)(h % a.bias_H)) * N * N +
                    (size_t)(i < N ? i : 0) * N;
     }
-    const ExpConst c = make_exp_const(a);
-    RowState<D> st;
-#pragma unroll
-    for (int t = 0; t < D / 32; ++t) st.acc[t] = v16i{0};
-    st.l = 0;
-    st.m = kMInit;
-
     // First tile (no rescale), the remaining full tiles as one straight-line loop body, then the
     // ragged tile if the sequence does not end on a tile boundary.
     const int n_full = N / BC, rem = N - n_full * BC;
 #define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
-    process_tile<D, BC, BIAS, XM, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,              \
-                                                     sV + (J_) * BC, VROW, NV_, sT, a.lut_xp,                \
-                                                     BIAS ? bias_row + (J_) * BC : nullptr, c, a.a_mul, li, g)
+    if (active)                                                                                              \
+    process_tile<D, BC, BIAS, XM, SB, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,          \
+                                                     sV + (J_) * BC, VROW, NV_, a.lut_xp,                    \
+                                                     BIAS ? bias_row + (J_) * BC : nullptr, c, a.a_mul, li, g, zb)
+    // Pipelined mode, around tile j: tile j+1 (loaded while tile j-1 was processed) goes to LDS and
+    // the loads of tile j+2 are issued before the arithmetic of tile j; the barrier after it
+    // publishes tile j+1, which every wavefront wrote long before.
+#define QF_PRE(J_)                                                                                           \
+    if (pipelined && (J_) + 1 < n_tiles) {                                                                   \
+        write_tile((J_) + 1, pf);                                                                            \
+        if ((J_) + 2 < n_tiles) load_tile((J_) + 2, pf);                                                     \
+    }
+#define QF_POST(J_)                                                                                          \
+    if (pipelined && (J_) + 1 < n_tiles) __syncthreads();
     if (n_full > 0) {
+        QF_PRE(0)
         QF_TILE(true, true, 0, BC);
-        for (int j = 1; j < n_full; ++j) QF_TILE(true, false, j, BC);
+        QF_POST(0)
+        for (int j = 1; j < n_full; ++j) {
+            QF_PRE(j)
+            QF_TILE(true, false, j, BC);
+            QF_POST(j)
+        }
         if (rem > 0) QF_TILE(false, false, n_full, rem);
     } else {
         QF_TILE(false, true, 0, rem);
     }
 #undef QF_TILE
+#undef QF_PRE
+#undef QF_POST
+    if (!active) return;
     if (i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
     if (NARROW) normalise_store<D, 16>(st, Orow, g, a.out_round != 0);
@@ -552,9 +743,10 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
     }
     const ExpConst c = make_exp_const(a);
-    RowState<D> st;
+    v16i zb;   // starts the accumulators at their offset 2^31 in the first tile
 #pragma unroll
-    for (int t = 0; t < D / 32; ++t) st.acc[t] = v16i{0};
+    for (int v = 0; v < 16; ++v) zb[v] = kAccBias;
+    RowState<D> st;
     st.l = 0;
     st.m = kMInit;
 
@@ -577,11 +769,11 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         const int n_valid = min(BC, N - c0);
         const int32_t* brow = BIAS ? bias_row + c0 : nullptr;
         if (j == 0)
-            process_tile<D, BC, BIAS, kExpShift, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, nullptr, 0, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, kExpShift, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, a.a_mul, li, g, zb);
         else if (n_valid == BC)
-            process_tile<D, BC, BIAS, kExpShift, true, false>(st, qreg, sK, KROW, sV, VROW, BC, nullptr, 0, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, kExpShift, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, 0, brow, c, a.a_mul, li, g, zb);
         else
-            process_tile<D, BC, BIAS, kExpShift, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, nullptr, 0, brow, c, a.a_mul, li, g);
+            process_tile<D, BC, BIAS, kExpShift, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, a.a_mul, li, g, zb);
     }
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
@@ -658,9 +850,9 @@ static size_t resident_lds_bytes(int N, int d, int heads, int table_bytes, int l
 }
 
 int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* a) {
-    (void)kv_tile;
     a->resident = resident_lds_bytes(N, d, 1, 0, lds_limit) != 0;
     a->heads_per_wg = 1;
+    a->pipelined = 0;
     if (a->resident) {
         const int nblk = (N + 31) / 32;
         const int max_waves = N <= 256 ? resident_max_waves<true>() : resident_max_waves<false>();
@@ -676,6 +868,10 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
             while (hp > 1 && resident_lds_bytes(N, d, hp, 0, lds_limit / 4) == 0) --hp;
             a->heads_per_wg = hp;
         }
+        // Tile-by-tile staging needs a second KV tile to overlap with and one staging item per
+        // thread: 32-byte pieces of K plus 4x8 blocks of V of one tile.
+        const int items = kv_tile * d / 16;
+        a->pipelined = a->heads_per_wg == 1 && N > kv_tile && items <= 64 * waves;
     } else {
         a->rows_per_wg = kStreamRows;
         a->waves_per_head = kStreamWaves;

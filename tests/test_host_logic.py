@@ -86,3 +86,36 @@ def test_scale_release_32bit_form():
     a[:3] = [0, 65536, 1]
     assert np.all(((x << 2) * (a << 14)) >> 32 == (x * a) >> 16)
     assert max(abs(x << 2)) < (1 << 31) and max(a << 14) < (1 << 31)
+
+
+def test_scale_release_on_offset_accumulators():
+    """With y = x + 2^31 (uint32), mul_hi_u32(y, A) + C (mod 2^32) == floor(x alpha16 / 2^16) + 2^31,
+    where A = alpha16 << 16, C = 2^31 - A/2, and for the identity alpha16 = 2^16: A = 2^32 - 1, C = 1."""
+    rng = np.random.default_rng(4)
+    x = rng.integers(-(1 << 26) + 1, 1 << 26, size=40000).astype(object)
+    x[:6] = [0, 1, -1, (1 << 26) - 1, -(1 << 26) + 1, 12345]
+    a = rng.integers(0, 65537, size=40000).astype(object)
+    a[:8] = [0, 65536, 1, 65535, 32768, 32767, 65536, 65536]
+    a[20000:30000] = 65536
+    one = a >> 16
+    A = ((a << 16) - one) & M32
+    C = ((1 << 31) - (a << 15) + one) & M32
+    y = (x + (1 << 31)) & M32
+    got = (((y * A) >> 32) + C) & M32
+    want = (((x * a) >> 16) + (1 << 31)) & M32
+    assert np.all(got == want)
+
+
+def test_offset_scores_give_the_table_index_in_one_saturating_subtraction():
+    """max(0, s - m + x_p) == usub_sat(s + 2^31, m + 2^31 - x_p) on uint32 for scores in (-2^21, 2^21);
+    a padded column stored as 0 gives index 0; the unsigned maximum orders offset scores like signed ones."""
+    rng = np.random.default_rng(5)
+    for _ in range(20000):
+        x_p = int(rng.integers(1, 40960))
+        s = int(rng.integers(-(1 << 21) + 1, 1 << 21))
+        m = int(rng.integers(s, 1 << 21))
+        sb, mb = (s + (1 << 31)) & M32, (m + (1 << 31)) & M32
+        edge = (mb - x_p) & M32
+        assert max(0, sb - edge) == max(0, s - m + x_p) <= x_p
+        assert max(0, 0 - edge) == 0
+        assert (sb <= mb) and ((-(1 << 21) + (1 << 31)) & M32) <= sb
