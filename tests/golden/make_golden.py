@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 
 import oracle  # noqa: E402
-from workloads import CONFIG_ORDER, make_workload  # noqa: E402
+from workloads import BASELINE_CONFIGS as CONFIG_ORDER, make_workload  # noqa: E402
 
 BATCH = {"deit_tiny_b1": 1, "vit_b16_b64": 2, "deit_b384_b32": 1, "swin_t_s1_b64": 128,
          "vit_l384_heavy": 1}

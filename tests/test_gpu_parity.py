@@ -70,6 +70,9 @@ SHAPES = [
     ((1, 2, 128, 64), 128), ((1, 2, 129, 64), 128), ((2, 3, 197, 64), 64), ((1, 2, 197, 64), 128),
     ((1, 2, 200, 32), 128), ((1, 2, 257, 64), 64), ((1, 2, 300, 32), 64), ((1, 1, 577, 64), 64),
     ((1, 1, 577, 64), 128), ((1, 1, 1030, 64), 64), ((3, 5, 49, 32), 64), ((3, 5, 49, 32), 128),
+    # tile-by-tile staging: the fewest wavefronts that allow it, full tiles only, one odd row
+    ((1, 2, 100, 64), 64), ((1, 2, 128, 64), 64), ((2, 2, 160, 64), 64), ((1, 2, 256, 64), 64),
+    ((1, 2, 193, 64), 64), ((1, 2, 384, 64), 128), ((1, 1, 640, 64), 64),
 ]
 
 
@@ -186,6 +189,22 @@ def test_benchmark_workloads_full_size(gpu, name):
     p = oracle.derive_params(wl.sQ, wl.sK, wl.shape[-1])
     if name == "vit_l384_heavy":
         assert p.x_shift > 0
+    for tile in wl.kv_tiles:
+        check(gpu, wl.Q, wl.K, wl.V, p, tile, bias=wl.bias, label=name)
+
+
+# ------------------------------- the paper's own workload table at batch 1 and 8 (small launches)
+
+
+from workloads import TABLE1_CONFIGS  # noqa: E402
+
+
+@pytest.mark.parametrize("name", TABLE1_CONFIGS)
+def test_table1_workloads(gpu, name):
+    """Table 1 (A1-A7) at batch 1 and 8: few workgroups, windowed ones with relative-position bias
+    and shifted-window exclusion, several windows per workgroup."""
+    wl = make_workload(name)
+    p = oracle.derive_params(wl.sQ, wl.sK, wl.shape[-1])
     for tile in wl.kv_tiles:
         check(gpu, wl.Q, wl.K, wl.V, p, tile, bias=wl.bias, label=name)
 

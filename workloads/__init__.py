@@ -107,7 +107,7 @@ def swin_window_bias(rng, heads, d, sQ, sK, n_windows=64, win=7):
     return bias, bias_real, excluded
 
 
-# name -> (shape [B,H,N,d], dist, sigma, outlier_frac, kv_tiles, windowed)
+# name -> (shape [B,H,N,d], dist, sigma, outlier_frac, kv_tiles, windowed: False, True (64 windows) or the window count)
 CONFIGS = {
     "deit_tiny_b1":   ((1, 3, 197, 64),   "normal",     1.0, 0.0,  (64,),     False),
     "vit_b16_b64":    ((64, 12, 197, 64), "normal",     1.0, 0.0,  (64,),     False),
@@ -115,12 +115,31 @@ CONFIGS = {
     "swin_t_s1_b64":  ((4096, 3, 49, 32), "normal",     1.0, 0.0,  (64,),     True),
     "vit_l384_heavy": ((16, 16, 577, 64), "student_t3", 1.0, 0.01, (64,),     False),
 }
+# The attention workloads of Table 1 at the paper's own batch sizes 1 and 8 (small, latency-bound
+# launches).  Windowed ones give the number of windows per image: B = batch * windows, and the
+# bias holds one [H,N,N] slice per window position.  The last stage has a single window per image,
+# hence no shifted-window mask.
+#   name -> (heads, N, d, windows per image or 0)
+TABLE1 = {
+    "a1_deit_t": (3, 197, 64, 0),
+    "a2_deit_s": (6, 197, 64, 0),
+    "a3_vit_b":  (12, 197, 64, 0),
+    "a4_swin_s1": (3, 49, 32, 64),
+    "a5_swin_s2": (6, 49, 32, 16),
+    "a6_swin_s3": (12, 49, 32, 4),
+    "a7_swin_s4": (24, 49, 32, 1),
+}
+for _name, (_h, _n, _d, _win) in TABLE1.items():
+    for _b in (1, 8):
+        CONFIGS["%s_b%d" % (_name, _b)] = ((_b * max(_win, 1), _h, _n, _d), "normal", 1.0, 0.0, (64,), _win)
 CONFIG_ORDER = list(CONFIGS)
 HEADLINE = "vit_b16_b64"
+BASELINE_CONFIGS = CONFIG_ORDER[:5]           # the five benchmark configurations
+TABLE1_CONFIGS = CONFIG_ORDER[5:]             # Table 1 at batch 1 and 8
 
 
 def make_workload(name: str, batch: Optional[int] = None) -> Workload:
-    """Build one of the five named workloads; ``batch`` overrides B (tests use smaller ones).
+    """Build one of the named workloads; ``batch`` overrides B (tests use smaller ones).
 
     Seed = 1000 + position of the workload in CONFIG_ORDER (1-based).
     """
@@ -131,5 +150,6 @@ def make_workload(name: str, batch: Optional[int] = None) -> Workload:
     Q, K, V, sQ, sK, sV, rng = make_qkv(shape, seed, dist, sigma, ofrac)
     wl = Workload(name, Q, K, V, sQ, sK, sV, kv_tiles, meta={"seed": seed, "dist": dist})
     if windowed:
-        wl.bias, wl.bias_real, wl.excluded = swin_window_bias(rng, shape[1], shape[3], sQ, sK)
+        n_windows = 64 if windowed is True else int(windowed)
+        wl.bias, wl.bias_real, wl.excluded = swin_window_bias(rng, shape[1], shape[3], sQ, sK, n_windows=n_windows)
     return wl
