@@ -52,6 +52,8 @@ def _load():
         lib.oracle_qflash_attention.restype = ci
         lib.oracle_qflash_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci,
                                                 pp, vp, vp, vp, vp, ci]
+        lib.oracle_qflash_attention_per_head.restype = ci
+        lib.oracle_qflash_attention_per_head.argtypes = lib.oracle_qflash_attention.argtypes
         _lib = lib
     return _lib
 
@@ -84,10 +86,11 @@ def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
-def qflash_attention(Q, K, V, p: OracleParams, kv_tile: int, bias=None, nthreads: int = 0,
+def qflash_attention(Q, K, V, p, kv_tile: int, bias=None, nthreads: int = 0,
                      return_state: bool = False):
     """Algorithm 1 on int8 arrays of shape [B,H,N,d]; returns int8 [B,H,N,d].
 
+    ``p``: one OracleParams (per-tensor scales) or a sequence of H of them (per-head scales).
     ``bias``: None or int32 [bias_B, bias_H, N, N] (INT32_MIN excludes a column).
     With ``return_state`` also returns dict(O_acc, l, m, violations) of int64 arrays.
     """
@@ -109,9 +112,16 @@ def qflash_attention(Q, K, V, p: OracleParams, kv_tile: int, bias=None, nthreads
     l = np.zeros((B, H, N), dtype=np.int64) if return_state else None
     m = np.zeros((B, H, N), dtype=np.int64) if return_state else None
     viol = np.zeros(1, dtype=np.int64)
-    rc = _load().oracle_qflash_attention(
+    if isinstance(p, OracleParams):
+        fn, cparams = _load().oracle_qflash_attention, _cp(p)
+    else:
+        p = list(p)
+        if len(p) != H:
+            raise ValueError("per-head constants: need one OracleParams per head")
+        fn, cparams = _load().oracle_qflash_attention_per_head, (_CParams * H)(*[_cp(x) for x in p])
+    rc = fn(
         Q.ctypes.data, K.ctypes.data, V.ctypes.data, O.ctypes.data, bias_ptr, bias_B, bias_H,
-        B, H, N, d, int(kv_tile), ctypes.byref(_cp(p)),
+        B, H, N, d, int(kv_tile), ctypes.cast(ctypes.byref(cparams), ctypes.POINTER(_CParams)),
         O_acc.ctypes.data if return_state else None,
         l.ctypes.data if return_state else None,
         m.ctypes.data if return_state else None,

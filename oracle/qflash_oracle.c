@@ -129,14 +129,14 @@ int64_t oracle_scale_release(int64_t acc, int64_t alpha16)
  *   nthreads   OpenMP threads over (b,h); <= 0 means the OpenMP default.
  * Returns 0, or -1 on an invalid argument.
  */
-int oracle_qflash_attention(const int8_t *Q, const int8_t *K, const int8_t *V,
-                            int8_t *O, const int32_t *bias, int bias_B, int bias_H,
-                            int B, int H, int N, int d, int kv_tile,
-                            const oracle_params *p,
-                            int64_t *O_acc, int64_t *l_out, int64_t *m_out,
-                            int64_t *violations, int nthreads)
+static int attention_impl(const int8_t *Q, const int8_t *K, const int8_t *V,
+                          int8_t *O, const int32_t *bias, int bias_B, int bias_H,
+                          int B, int H, int N, int d, int kv_tile,
+                          const oracle_params *p_all, int p_per_head,
+                          int64_t *O_acc, int64_t *l_out, int64_t *m_out,
+                          int64_t *violations, int nthreads)
 {
-    if (!Q || !K || !V || !O || !p) return -1;
+    if (!Q || !K || !V || !O || !p_all) return -1;
     if (B < 1 || H < 1 || N < 1 || d < 1 || kv_tile < 1) return -1;
     if (bias && (bias_B < 1 || bias_H < 1)) return -1;
 
@@ -151,6 +151,8 @@ int oracle_qflash_attention(const int8_t *Q, const int8_t *K, const int8_t *V,
 #pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad_total)
     for (int bh = 0; bh < B * H; ++bh) {
         const int b = bh / H, h = bh % H;
+        /* per-tensor constants, or those of head h (Section 3.2 / Appendix C3: per-head scales) */
+        const oracle_params *p = p_per_head ? p_all + h : p_all;
         const int8_t *Qh = Q + (size_t)bh * N * d;
         const int8_t *Kh = K + (size_t)bh * N * d;
         const int8_t *Vh = V + (size_t)bh * N * d;
@@ -244,6 +246,34 @@ int oracle_qflash_attention(const int8_t *Q, const int8_t *K, const int8_t *V,
     }
     if (violations) *violations = bad_total;
     return 0;
+}
+
+int oracle_qflash_attention(const int8_t *Q, const int8_t *K, const int8_t *V,
+                            int8_t *O, const int32_t *bias, int bias_B, int bias_H,
+                            int B, int H, int N, int d, int kv_tile,
+                            const oracle_params *p,
+                            int64_t *O_acc, int64_t *l_out, int64_t *m_out,
+                            int64_t *violations, int nthreads)
+{
+    return attention_impl(Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, 0,
+                          O_acc, l_out, m_out, violations, nthreads);
+}
+
+/*
+ * The same with one set of integer constants per head: p[h] serves every (b, h) pair of head h
+ * (per-head quantisation, Section 3.2 and Appendix C3: Q, K and V of a head share one scale
+ * each, so the running maximum still compares like with like).  The output of head h has scale
+ * s_V of that head.  Everything else as above.
+ */
+int oracle_qflash_attention_per_head(const int8_t *Q, const int8_t *K, const int8_t *V,
+                                     int8_t *O, const int32_t *bias, int bias_B, int bias_H,
+                                     int B, int H, int N, int d, int kv_tile,
+                                     const oracle_params *p /* H entries */,
+                                     int64_t *O_acc, int64_t *l_out, int64_t *m_out,
+                                     int64_t *violations, int nthreads)
+{
+    return attention_impl(Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, 1,
+                          O_acc, l_out, m_out, violations, nthreads);
 }
 
 int oracle_num_threads(void)

@@ -363,3 +363,58 @@ def test_result_does_not_depend_on_thread_count_or_batching():
     c = np.stack([oracle.qflash_attention(Q[i:i + 1], K[i:i + 1], V[i:i + 1], p, 32)[0]
                   for i in range(3)])
     assert np.array_equal(a, b) and np.array_equal(a, c)
+
+
+# ------------------------------------------------------------- per-head constants (Appendix C3)
+
+
+def test_per_head_constants_equal_head_by_head_runs():
+    """With one set of constants per head, head h must be exactly what the per-tensor routine
+    gives on the slice [:, h] with constants h: pins the head indexing (and nothing else is new).
+    Heads differ strongly in scale, one of them needs x_shift > 0; bias with bias_H = H and = 1."""
+    rng = np.random.default_rng(77)
+    B, H, N, d, tile = 2, 4, 150, 32, 64
+    Q, K, V = (rng.integers(-127, 128, size=(B, H, N, d)).astype(np.int8) for _ in range(3))
+    sQ = [0.004, 0.02, 0.11, 2.5]
+    ps = [derive_params(sQ[h], 0.03 * (h + 1), d) for h in range(H)]
+    assert len({p.s_inv for p in ps}) == H and ps[-1].x_shift > 0 and ps[0].x_shift == 0
+    for bias_H in (None, H, 1):
+        bias = None
+        if bias_H is not None:
+            bias = rng.integers(-2000, 2000, size=(1, bias_H, N, N)).astype(np.int32)
+            bias[0, :, :, 5] = EXCLUDED
+        got = oracle.qflash_attention(Q, K, V, ps, tile, bias=bias)
+        for h in range(H):
+            bh = None if bias is None else bias[:, (h % bias_H):(h % bias_H) + 1]
+            want = oracle.qflash_attention(Q[:, h:h + 1], K[:, h:h + 1], V[:, h:h + 1], ps[h], tile, bias=bh)
+            assert np.array_equal(got[:, h:h + 1], want), (bias_H, h)
+    # the constants really are per head: a different assignment changes the result
+    other = oracle.qflash_attention(Q, K, V, ps[::-1], tile)
+    assert not np.array_equal(other, oracle.qflash_attention(Q, K, V, ps, tile))
+
+
+def test_per_head_with_equal_constants_is_the_per_tensor_result():
+    wl = make_workload("deit_tiny_b1")
+    p = derive_params(wl.sQ, wl.sK, wl.shape[-1])
+    a = oracle.qflash_attention(wl.Q, wl.K, wl.V, p, 64)
+    b = oracle.qflash_attention(wl.Q, wl.K, wl.V, [p] * wl.shape[1], 64)
+    assert np.array_equal(a, b)
+    with pytest.raises(ValueError):
+        oracle.qflash_attention(wl.Q, wl.K, wl.V, [p] * (wl.shape[1] - 1), 64)
+
+
+def test_per_head_quantisation_improves_fidelity_when_heads_differ():
+    """The point of per-head scales: heads of different range, quantised per tensor, lose the
+    quiet heads; per head they keep them.  Cosine against float softmax attention on the
+    dequantised per-head inputs, worst head."""
+    from oracle.bruteforce import float_attention
+    from workloads import make_qkv, head_gains
+    shape = (1, 4, 48, 32)
+    Qh, Kh, Vh, sQ, sK, sV, _ = make_qkv(shape, 5, per_head=True, head_gain=head_gains(4))
+    ps = [derive_params(sQ[h], sK[h], 32) for h in range(4)]
+    out = oracle.qflash_attention(Qh, Kh, Vh, ps, 16)
+    for h in range(4):
+        ref = float_attention(Qh[:, h:h + 1], Kh[:, h:h + 1], Vh[:, h:h + 1], sQ[h], sK[h], sV[h])[0, 0]
+        got = (out[0, h].astype(np.float64) + 0.5) * sV[h]
+        cos = float((ref * got).sum() / np.sqrt((ref * ref).sum() * (got * got).sum()))
+        assert cos > 0.995, (h, cos)

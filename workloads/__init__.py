@@ -26,7 +26,7 @@ class Workload:
     Q: np.ndarray                 # int8 [B,H,N,d]
     K: np.ndarray
     V: np.ndarray
-    sQ: float
+    sQ: float                     # per-tensor scale, or array [H] in the per-head variant
     sK: float
     sV: float
     kv_tiles: tuple               # KV tile sizes this workload is run with
@@ -50,6 +50,16 @@ def quantize_per_tensor(x: np.ndarray):
     return q, s
 
 
+def quantize_per_head(x: np.ndarray):
+    """Eq. 1-2 with one scale per head (axis 1 of [B,H,N,d]): returns int8 array and scales [H]."""
+    H = x.shape[1]
+    q = np.zeros(x.shape, dtype=np.int8)
+    s = np.ones(H, dtype=np.float64)
+    for h in range(H):
+        q[:, h], s[h] = quantize_per_tensor(x[:, h])
+    return q, s
+
+
 def _draw(rng, shape, dist, sigma=1.0, outlier_frac=0.0, outlier_gain=8.0):
     if dist == "normal":
         x = rng.standard_normal(size=shape, dtype=np.float32) * np.float32(sigma)
@@ -67,13 +77,17 @@ def _draw(rng, shape, dist, sigma=1.0, outlier_frac=0.0, outlier_gain=8.0):
     return x
 
 
-def make_qkv(shape, seed, dist="normal", sigma=1.0, outlier_frac=0.0):
-    """Q, K, V drawn in that order from one generator, each quantised per tensor."""
+def make_qkv(shape, seed, dist="normal", sigma=1.0, outlier_frac=0.0, per_head=False, head_gain=None):
+    """Q, K, V drawn in that order from one generator, each quantised per tensor (or per head:
+    the scales are then arrays [H]; ``head_gain`` [H] multiplies the real values of each head
+    first, so that heads differ in range the way trained heads do)."""
     rng = np.random.default_rng(seed)
     out = []
     for _ in range(3):
         x = _draw(rng, shape, dist, sigma, outlier_frac)
-        out.append(quantize_per_tensor(x))
+        if head_gain is not None:
+            x = x * np.asarray(head_gain, dtype=np.float32)[None, :, None, None]
+        out.append(quantize_per_head(x) if per_head else quantize_per_tensor(x))
     (Q, sQ), (K, sK), (V, sV) = out
     return Q, K, V, sQ, sK, sV, rng
 
@@ -138,7 +152,12 @@ BASELINE_CONFIGS = CONFIG_ORDER[:5]           # the five benchmark configuration
 TABLE1_CONFIGS = CONFIG_ORDER[5:]             # Table 1 at batch 1 and 8
 
 
-def make_workload(name: str, batch: Optional[int] = None) -> Workload:
+def head_gains(H: int) -> np.ndarray:
+    """Deterministic spread of per-head ranges, 1/4 .. 4 (geometric), used by the per-head variant."""
+    return np.exp2(np.linspace(-2.0, 2.0, H)) if H > 1 else np.ones(1)
+
+
+def make_workload(name: str, batch: Optional[int] = None, per_head: bool = False) -> Workload:
     """Build one of the named workloads; ``batch`` overrides B (tests use smaller ones).
 
     Seed = 1000 + position of the workload in CONFIG_ORDER (1-based).
@@ -147,6 +166,16 @@ def make_workload(name: str, batch: Optional[int] = None) -> Workload:
     if batch is not None:
         shape = (int(batch),) + tuple(shape[1:])
     seed = 1000 + CONFIG_ORDER.index(name) + 1
+    if per_head:
+        # per-head variant (Appendix C3): heads get different ranges and their own scales;
+        # sQ, sK, sV are arrays [H].  Not offered for the windowed workloads (their integer bias
+        # is expressed in the score unit of one tensor-wide scale).
+        if windowed:
+            raise ValueError("per-head variant is defined for the non-windowed workloads")
+        Q, K, V, sQ, sK, sV, rng = make_qkv(shape, seed, dist, sigma, ofrac, per_head=True,
+                                            head_gain=head_gains(shape[1]))
+        return Workload(name + "/per_head", Q, K, V, sQ, sK, sV, kv_tiles,
+                        meta={"seed": seed, "dist": dist, "per_head": True})
     Q, K, V, sQ, sK, sV, rng = make_qkv(shape, seed, dist, sigma, ofrac)
     wl = Workload(name, Q, K, V, sQ, sK, sV, kv_tiles, meta={"seed": seed, "dist": dist})
     if windowed:
