@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the integer-only fused attention forward pass on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kv-tile T] [--per-head]
+                    [--no-cpu-baseline]
 
 One step = one pass of the whole hot path (a single fused kernel launch: both int8 matmuls, the
 integer online softmax, normalisation and the int8 store) over one batch of the workload.  Inputs
@@ -37,6 +38,9 @@ def main():
     ap.add_argument("--workload", default=None)
     ap.add_argument("--kv-tile", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-head", action="store_true",
+                    help="per-head variant of the workload: heads of different range, one set of "
+                         "integer constants per head (qflash_attention_per_head)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device-to-device copy, so that a rocprofv3 --pmc "
                          "trace of this command holds a kernel of known HBM traffic")
@@ -56,10 +60,13 @@ def main():
         sys.exit(1)
     qf.load_library()           # fails loudly when the HIP library is missing
     name = args.workload or HEADLINE
-    wl = make_workload(name)
+    wl = make_workload(name, per_head=args.per_head)
     B, H, N, d = wl.shape
     tile = args.kv_tile or wl.kv_tiles[0]
-    params = qf.qflash_params_from_scales(wl.sQ, wl.sK, wl.sV, d)
+    if args.per_head:
+        params = [qf.qflash_params_from_scales(wl.sQ[h], wl.sK[h], wl.sV[h], d) for h in range(H)]
+    else:
+        params = qf.qflash_params_from_scales(wl.sQ, wl.sK, wl.sV, d)
     dev = torch.device("cuda:0")
 
     io_bytes = 4 * B * H * N * d                       # Q, K, V read once, O written once
@@ -130,7 +137,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8/int32",
         "data": "synthetic",
         "config": {"workload": name, "B": B, "H": H, "N": N, "d": d, "kv_tile": tile,
-                   "bias": wl.bias is not None, "input_sets_rotated": len(sets)},
+                   "bias": wl.bias is not None, "scales": "per_head" if args.per_head else "per_tensor",
+                   "input_sets_rotated": len(sets)},
         "kernel_us_events": kern_s * 1e6,
         "hot_cache": {"kernel_us_events": ev_hot / args.steps * 1e6,
                       "tops": ops / (ev_hot / args.steps) / 1e12},
@@ -143,8 +151,12 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        po = oracle.derive_params(wl.sQ, wl.sK, d)
-        assert po.astuple() == params.astuple()
+        if args.per_head:
+            po = [oracle.derive_params(wl.sQ[h], wl.sK[h], d) for h in range(H)]
+            assert all(a.astuple() == b.astuple() for a, b in zip(po, params))
+        else:
+            po = oracle.derive_params(wl.sQ, wl.sK, d)
+            assert po.astuple() == params.astuple()
         reps, t_cpu, ref = 0, 0.0, None
         while t_cpu < 3.0 and reps < 20:               # a few full passes of the same workload
             t0 = time.perf_counter()

@@ -31,6 +31,7 @@ extern "C" {
 #define QFLASH_ERR_ALIGN   (-8)  /* Q, K, V or O is not 16-byte aligned, bias not 4-byte aligned  */
 
 #define QFLASH_MAX_N       4096  /* 128*127*N must stay below 2^31 with margin                    */
+#define QFLASH_MAX_PARAM_HEADS 64 /* most heads qflash_attention_per_head accepts                 */
 #define QFLASH_EXCLUDED    INT32_MIN  /* bias value that removes a (query, key) pair              */
 
 typedef struct qflash_ctx qflash_ctx;   /* opaque; created and destroyed by the library */
@@ -112,6 +113,24 @@ int qflash_attention(qflash_ctx* ctx,
                      const int32_t* bias, int bias_B, int bias_H,
                      int B, int H, int N, int d, int kv_tile,
                      const qflash_params* p, void* hip_stream);
+
+/*
+ * The same pass with per-head quantisation (Section 3.2 and Appendix C3: per-tensor and per-head
+ * are the granularities under which the integer running maximum still compares like with like).
+ * p points to H entries (host); head h of every batch element uses p[h], and its output has the
+ * scale s_V of that head.  All entries must share out_round.  H <= QFLASH_MAX_PARAM_HEADS.
+ * bias, if given, is added to the integer score of each head as is, i.e. it has to be expressed
+ * in that head's score unit.  Everything else as for qflash_attention; with workgroups that
+ * serve several short sequences at once (N <= 64 or so) the weights are always computed
+ * arithmetically.
+ * Errors: as qflash_attention; SHAPE also for H > QFLASH_MAX_PARAM_HEADS, PARAM also for
+ * entries that differ in out_round.
+ */
+int qflash_attention_per_head(qflash_ctx* ctx,
+                              const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
+                              const int32_t* bias, int bias_B, int bias_H,
+                              int B, int H, int N, int d, int kv_tile,
+                              const qflash_params* p /* host, H entries */, void* hip_stream);
 
 /*
  * Destroy a context.  NULL is accepted (returns QFLASH_OK).  Destroying a context twice, or a

@@ -15,7 +15,9 @@ ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, 
        "CTX": -7, "ALIGN": -8}
 
 EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
-           "qflash_destroy", "qflash_strerror"]
+           "qflash_attention_per_head", "qflash_destroy", "qflash_strerror"]
+
+MAX_PARAM_HEADS = 64
 
 CFG_EXP_TABLE = 1
 
@@ -58,6 +60,8 @@ def load_library():
         lib.qflash_create.restype = ci
         lib.qflash_create.argtypes = [ctypes.POINTER(vp), ci]
         lib.qflash_attention.restype = ci
+        lib.qflash_attention_per_head.restype = ci
+        lib.qflash_attention_per_head.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
         lib.qflash_attention.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
         lib.qflash_configure.restype = ci
         lib.qflash_configure.argtypes = [vp, ci, ci]
@@ -107,11 +111,7 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def qflash_attention(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, bias=None,
-                     stream: Optional[int] = None) -> None:
-    """Enqueue one forward pass.  Q, K, V, O: contiguous int8 CUDA tensors [B,H,N,d];
-    bias: None or contiguous int32 CUDA tensor [bias_B,bias_H,N,N].  ``stream`` is a raw
-    hipStream_t value (default: torch's current stream on the tensors' device)."""
+def _marshal(Q, K, V, O, bias, stream):
     import torch
     for name, t in (("Q", Q), ("K", K), ("V", V), ("O", O)):
         if t.dtype != torch.int8 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
@@ -127,12 +127,33 @@ def qflash_attention(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, b
         bias_B, bias_H = int(bias.shape[0]), int(bias.shape[1])
     if stream is None:
         stream = torch.cuda.current_stream(Q.device).cuda_stream
-    rc = load_library().qflash_attention(
-        ctypes.c_void_p(ctx), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(bias), bias_B, bias_H,
-        int(B), int(H), int(N), int(d), int(kv_tile), ctypes.byref(params),
-        ctypes.c_void_p(stream))
+    return (_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(bias), bias_B, bias_H,
+            int(B), int(H), int(N), int(d)), ctypes.c_void_p(stream)
+
+
+def qflash_attention(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, bias=None,
+                     stream: Optional[int] = None) -> None:
+    """Enqueue one forward pass.  Q, K, V, O: contiguous int8 CUDA tensors [B,H,N,d];
+    bias: None or contiguous int32 CUDA tensor [bias_B,bias_H,N,N].  ``stream`` is a raw
+    hipStream_t value (default: torch's current stream on the tensors' device)."""
+    args, st = _marshal(Q, K, V, O, bias, stream)
+    rc = load_library().qflash_attention(ctypes.c_void_p(ctx), *args, int(kv_tile), ctypes.byref(params), st)
     if rc != 0:
         raise QFlashError(rc, "qflash_attention")
+
+
+def qflash_attention_per_head(ctx: int, Q, K, V, O, params, kv_tile: int, bias=None,
+                              stream: Optional[int] = None) -> None:
+    """The same with one ``QFlashParams`` per head (a sequence of H of them)."""
+    args, st = _marshal(Q, K, V, O, bias, stream)
+    params = list(params)
+    if len(params) != args[8]:
+        raise ValueError("need one QFlashParams per head")
+    arr = (QFlashParams * len(params))(*params)
+    rc = load_library().qflash_attention_per_head(
+        ctypes.c_void_p(ctx), *args, int(kv_tile), ctypes.cast(arr, ctypes.POINTER(QFlashParams)), st)
+    if rc != 0:
+        raise QFlashError(rc, "qflash_attention_per_head")
 
 
 class Context:
@@ -145,7 +166,11 @@ class Context:
         qflash_configure(self.handle, key, value)
 
     def attention(self, Q, K, V, O, params, kv_tile, bias=None, stream=None):
-        qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
+        """``params``: one QFlashParams (per-tensor scales) or a sequence of H (per-head scales)."""
+        if isinstance(params, QFlashParams):
+            qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
+        else:
+            qflash_attention_per_head(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
 
     def close(self):
         if self.handle is not None:

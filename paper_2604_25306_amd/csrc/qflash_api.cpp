@@ -174,9 +174,26 @@ extern "C" int qflash_configure(qflash_ctx* ctx, int key, int value) {
     return QFLASH_OK;
 }
 
-extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
-                                int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B, int H,
-                                int N, int d, int kv_tile, const qflash_params* p, void* hip_stream) {
+namespace {
+
+// Clamp point of the exponent: smallest multiple of 2^-k at or below -20.5 octaves.  Above it
+// q <= 28 and every intermediate fits 24/32 bits; at and below it the numerator of Algorithm 2
+// (< 2^20) is shifted right by >= 20, so the exact result is 0.  Returns false if the constants
+// put it beyond 28.5 octaves.
+bool fill_head_consts(const qflash_params& p, QflashHeadConsts* h) {
+    h->x_shift = p.x_shift; h->s_inv = p.s_inv; h->exp_mul = p.exp_mul;
+    h->p_mul = p.p_mul; h->p_shift = p.p_shift; h->a_mul = p.a_mul;
+    const int64_t x0 = (41 * (int64_t)p.s_inv + ((int64_t)2 << p.x_shift) - 1) >> (p.x_shift + 1);
+    if ((x0 << p.x_shift) * 2 > 57 * (int64_t)p.s_inv) return false;
+    h->x_floor = (int)-x0;
+    h->lut = nullptr; h->lut_bytes = 0; h->lut_xp = 0;
+    return true;
+}
+
+// Shared by the per-tensor and the per-head entry points: n_p = 1 (p[0] serves every head) or H.
+int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
+                   const int32_t* bias, int bias_B, int bias_H, int B, int H, int N, int d, int kv_tile,
+                   const qflash_params* p, bool per_head, void* hip_stream) {
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit;
     {
@@ -189,29 +206,36 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
     if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
     if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+    if (per_head && H > QFLASH_MAX_PARAM_HEADS) return QFLASH_ERR_SHAPE;
     if (bias) {
         if (bias_B < 1 || bias_H < 1) return QFLASH_ERR_SHAPE;
         if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
     }
     if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
-    if (!params_ok(*p)) return QFLASH_ERR_PARAM;
+    const int n_p = per_head ? H : 1;
+    for (int h = 0; h < n_p; ++h) {
+        if (!params_ok(p[h])) return QFLASH_ERR_PARAM;
+        if (p[h].out_round != p[0].out_round) return QFLASH_ERR_PARAM;   // one rounding mode per call
+    }
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
     if (bias && ((uintptr_t)bias & 3u)) return QFLASH_ERR_ALIGN;
 
+    static_assert(QFLASH_MAX_PARAM_HEADS == kQflashMaxParamHeads, "header and kernel arguments disagree");
     QflashKernelArgs a;
     a.Q = Q; a.K = K; a.V = V; a.O = O;
     a.bias = bias;
     a.bias_B = bias ? bias_B : 1;
     a.bias_H = bias ? bias_H : 1;
     a.B = B; a.H = H; a.N = N;
-    a.x_shift = p->x_shift; a.s_inv = p->s_inv; a.exp_mul = p->exp_mul;
-    a.p_mul = p->p_mul; a.p_shift = p->p_shift; a.a_mul = p->a_mul; a.out_round = p->out_round;
-    // Clamp point of the exponent: smallest multiple of 2^-k at or below -20.5 octaves.
-    // Above it q <= 28 and every intermediate fits 24/32 bits; at and below it the numerator of
-    // Algorithm 2 (< 2^20) is shifted right by >= 20, so the exact result is 0.
-    const int64_t x0 = (41 * (int64_t)p->s_inv + ((int64_t)2 << p->x_shift) - 1) >> (p->x_shift + 1);
-    if ((x0 << p->x_shift) * 2 > 57 * (int64_t)p->s_inv) return QFLASH_ERR_PARAM;  // > 28.5 octaves
-    a.x_floor = (int)-x0;
+    a.out_round = p[0].out_round;
+    a.per_head = per_head ? 1 : 0;
+    bool all_k0 = true;
+    for (int h = 0; h < n_p; ++h) {
+        if (!fill_head_consts(p[h], &a.hc[h])) return QFLASH_ERR_PARAM;
+        all_k0 = all_k0 && p[h].x_shift == 0;
+    }
+    a.exp_mode = all_k0 ? 1 : 0;
+    a.lut_bytes_max = 0;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
 
     int cur = -1;
@@ -220,17 +244,26 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
         (void)hipGetLastError();
         return QFLASH_ERR_DEVICE;
     }
-    // Look-up mode: find (or build, once, on this stream) the weight table of these constants.
-    a.lut = nullptr; a.lut_bytes = 0; a.lut_xp = 0;
+    // Look-up mode: find (or build, once, on this stream) the weight table of each set of
+    // constants.  It is used only if every head gets one (the mode is uniform over a launch) and
+    // the largest fits LDS beside K and V.  Workgroups that serve several pairs share one table,
+    // which per-head constants cannot offer.
     int rc = 0;
     {
-        // weight is 0 at and below -8 octaves: x_p = ceil(8 s_inv / 2^k)
-        const int64_t x_p = (8 * (int64_t)p->s_inv + ((int64_t)1 << p->x_shift) - 1) >> p->x_shift;
-        const int n = (int)x_p + 1, n_padded = (n + 15) & ~15;
         std::lock_guard<std::mutex> lk(g_mu);
-        if (ctx->use_table && ctx->tables && a.resident && n_padded <= kTableMaxBytes &&
-            qflash_table_fits(a, d, n_padded, lds_limit)) {
-            const int32_t key[5] = {p->x_shift, p->s_inv, p->exp_mul, p->p_mul, p->p_shift};
+        bool ok = ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1);
+        int xp[kQflashMaxParamHeads], np_[kQflashMaxParamHeads], max_bytes = 0;
+        for (int h = 0; ok && h < n_p; ++h) {
+            // weight is 0 at and below -8 octaves: x_p = ceil(8 s_inv / 2^k)
+            const int64_t x_p = (8 * (int64_t)p[h].s_inv + ((int64_t)1 << p[h].x_shift) - 1) >> p[h].x_shift;
+            xp[h] = (int)x_p;
+            np_[h] = ((int)x_p + 1 + 15) & ~15;
+            if (np_[h] > kTableMaxBytes) ok = false;
+            if (np_[h] > max_bytes) max_bytes = np_[h];
+        }
+        ok = ok && qflash_table_fits(a, d, max_bytes, lds_limit);
+        for (int h = 0; ok && rc == 0 && h < n_p; ++h) {
+            const int32_t key[5] = {p[h].x_shift, p[h].s_inv, p[h].exp_mul, p[h].p_mul, p[h].p_shift};
             int slot = -1;
             for (int i = 0; i < ctx->n_slots; ++i)
                 if (ctx->slots[i].stream == hip_stream && std::memcmp(ctx->slots[i].key, key, sizeof key) == 0) {
@@ -241,19 +274,22 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
                 // The builder is enqueued under the lock, so no other host thread can enqueue a
                 // reader of this slot on the same stream ahead of it.
                 uint8_t* tbl = ctx->tables + (size_t)ctx->n_slots * kTableMaxBytes;
-                rc = qflash_launch_build_table(tbl, n, n_padded, (int)x_p, a, hip_stream);
+                rc = qflash_launch_build_table(tbl, xp[h] + 1, np_[h], xp[h], a.hc[h], hip_stream);
                 if (rc == 0) {
                     slot = ctx->n_slots++;
                     TableSlot& t = ctx->slots[slot];
                     std::memcpy(t.key, key, sizeof key);
-                    t.stream = hip_stream; t.n = n; t.n_padded = n_padded; t.x_p = (int)x_p;
+                    t.stream = hip_stream; t.n = xp[h] + 1; t.n_padded = np_[h]; t.x_p = xp[h];
                 }
             }
-            if (slot >= 0) {
-                a.lut = ctx->tables + (size_t)slot * kTableMaxBytes;
-                a.lut_bytes = n_padded;
-                a.lut_xp = (int)x_p;
-            }
+            if (slot < 0) { ok = false; break; }
+            a.hc[h].lut = ctx->tables + (size_t)slot * kTableMaxBytes;
+            a.hc[h].lut_bytes = np_[h];
+            a.hc[h].lut_xp = xp[h];
+        }
+        if (ok && rc == 0) {
+            a.exp_mode = 2;
+            a.lut_bytes_max = max_bytes;
         }
     }
     if (rc == 0) rc = qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
@@ -262,11 +298,26 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
     return QFLASH_OK;
 }
 
+}  // namespace
+
+extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
+                                int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B, int H,
+                                int N, int d, int kv_tile, const qflash_params* p, void* hip_stream) {
+    return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, false, hip_stream);
+}
+
+extern "C" int qflash_attention_per_head(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
+                                         int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B,
+                                         int H, int N, int d, int kv_tile, const qflash_params* p,
+                                         void* hip_stream) {
+    return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, true, hip_stream);
+}
+
 extern "C" const char* qflash_strerror(int code) {
     switch (code) {
         case QFLASH_OK: return "success";
         case QFLASH_ERR_NULL: return "a required pointer is NULL";
-        case QFLASH_ERR_SHAPE: return "unsupported shape (d in {32,64}, 1 <= N <= 4096, sizes below 2^31)";
+        case QFLASH_ERR_SHAPE: return "unsupported shape (d in {32,64}, 1 <= N <= 4096, sizes below 2^31, at most 64 heads with per-head constants)";
         case QFLASH_ERR_TILE: return "kv_tile must be 64 or 128";
         case QFLASH_ERR_PARAM: return "integer constants out of range or inconsistent";
         case QFLASH_ERR_DEVICE: return "no such GPU, not a gfx950 device, or HIP runtime error";

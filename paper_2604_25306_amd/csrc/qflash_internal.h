@@ -2,6 +2,21 @@
 #pragma once
 #include <stdint.h>
 
+// Integer constants of Algorithm 1 / 2 for one head, or for the whole tensor (see qflash_params).
+struct QflashHeadConsts {
+    int x_shift, s_inv, exp_mul, p_mul, p_shift, a_mul;
+    // x_floor <= 0: score differences below it are clamped to it.  Chosen on the host so that
+    // ShiftExp2 is exactly 0 at and below it, and every 32-bit intermediate is exact above it.
+    int x_floor;
+    // look-up mode (resident kernel only): table of int8 weights of these constants
+    int lut_xp;              // table index = score - running max + lut_xp, clamped at 0
+    int lut_bytes;           // bytes staged into LDS (multiple of 16)
+    const uint8_t* lut;      // nullptr = none
+};
+
+// Per-head constants travel in the kernel arguments (at most 4 KB in all).
+constexpr int kQflashMaxParamHeads = 64;
+
 struct QflashKernelArgs {
     const int8_t* Q;
     const int8_t* K;
@@ -10,11 +25,7 @@ struct QflashKernelArgs {
     const int32_t* bias;   // nullptr: no bias
     int bias_B, bias_H;
     int B, H, N;
-    // integer constants of Algorithm 1 / 2 (see qflash_params)
-    int x_shift, s_inv, exp_mul, p_mul, p_shift, a_mul, out_round;
-    // x_floor <= 0: score differences below it are clamped to it.  Chosen on the host so that
-    // ShiftExp2 is exactly 0 at and below it, and every 32-bit intermediate is exact above it.
-    int x_floor;
+    int out_round;
     // work decomposition: one unit = (batch*head, query tile); XCD x owns units
     // [x*units_per_xcd, (x+1)*units_per_xcd)
     int rows_per_wg, n_qtiles, n_units, units_per_xcd;
@@ -22,17 +33,19 @@ struct QflashKernelArgs {
     int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
     int pipelined;           // resident only: K/V tiles are staged one ahead of their use
-    // look-up mode (resident kernel only): table of int8 weights, nullptr = compute them
-    const uint8_t* lut;
-    int lut_bytes;           // bytes staged into LDS (multiple of 16)
-    int lut_xp;              // table index = score - running max + lut_xp, clamped at 0
+    // weight mode of the launch (uniform over heads): 2 = every head reads its table,
+    // 1 = arithmetic with x_shift == 0 for every head, 0 = arithmetic
+    int exp_mode;
+    int lut_bytes_max;       // LDS bytes reserved for the table: the largest of all heads
+    int per_head;            // 0: hc[0] serves every head; 1: head h uses hc[h] (H <= kQflashMaxParamHeads)
+    QflashHeadConsts hc[kQflashMaxParamHeads];
 };
 
 // Enqueue the forward kernel for head size d (32|64), KV tile (64|128).  Returns a hipError_t value.
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 
 // Choose the kernel variant for BH heads of N rows and fill the work decomposition fields
-// (resident, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd).
+// (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd).
 // Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
 int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);
@@ -40,5 +53,5 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
 // 1 if the resident kernel can also hold a weight table of table_bytes in LDS and copying it pays.
 int qflash_table_fits(const QflashKernelArgs& args, int d, int table_bytes, int lds_limit);
 
-// Enqueue the kernel that fills a weight table of n entries (n_padded bytes) for args' constants.
-int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashKernelArgs& args, void* stream);
+// Enqueue the kernel that fills a weight table of n entries (n_padded bytes) for the constants hc.
+int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashHeadConsts& hc, void* stream);

@@ -430,13 +430,19 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
         *(v4i*)(dst + 16 * q) = v4i{(int)ev[2 * q], (int)od[2 * q], (int)ev[2 * q + 1], (int)od[2 * q + 1]};
 }
 
-__device__ __forceinline__ ExpConst make_exp_const(const QflashKernelArgs& a) {
+__device__ __forceinline__ ExpConst make_exp_const(const QflashHeadConsts& h) {
     ExpConst c;
-    c.k = a.x_shift; c.s_inv = a.s_inv; c.x_floor = a.x_floor;
-    c.M_v = to_vgpr(a.exp_mul);
-    c.two_s_inv_v = to_vgpr(2 * a.s_inv);
-    c.p_mul_hi_v = to_vgpr(a.p_mul << (24 - a.p_shift));
+    c.k = h.x_shift; c.s_inv = h.s_inv; c.x_floor = h.x_floor;
+    c.M_v = to_vgpr(h.exp_mul);
+    c.two_s_inv_v = to_vgpr(2 * h.s_inv);
+    c.p_mul_hi_v = to_vgpr(h.p_mul << (24 - h.p_shift));
     return c;
+}
+
+// Constants of the head that (batch, head) pair bh belongs to.  bh is uniform over the wavefront,
+// so these are scalar loads from the kernel arguments.
+__device__ __forceinline__ const QflashHeadConsts& head_consts(const QflashKernelArgs& a, int bh) {
+    return a.hc[a.per_head ? bh % a.H : 0];
 }
 
 // 4x4 byte transpose: rows r[0..3] (byte f = feature f) -> o[f] = (r0.f, r1.f, r2.f, r3.f).
@@ -505,7 +511,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // pair's K and V^T are staged by its own wavefronts; the weight table is shared.
     // LDS: [weight table, lut_bytes (table mode only)] then per pair [K: npad x KROW] [V^T: D x VROW].
     // The table sits at offset 0 so that its index is the LDS address.
-    const int tbytes = XM == kExpTable ? a.lut_bytes : 0;
+    const int tbytes = XM == kExpTable ? a.lut_bytes_max : 0;   // LDS reserved for the table
 
     const int wg = blockIdx.x;
     const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
@@ -521,6 +527,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int qt = a.heads_per_wg > 1 ? 0 : unit % a.n_qtiles;
     const int bh = a.heads_per_wg > 1 ? unit * a.heads_per_wg + sub : unit / a.n_qtiles;
     const bool pair_valid = bh < a.B * a.H;
+    const QflashHeadConsts& hc = head_consts(a, pair_valid ? bh : 0);
     const int row0 = qt * a.rows_per_wg + (wave - sub * a.waves_per_head) * 32;
     const int i = row0 + li;
 
@@ -598,7 +605,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) qreg[s] = *(const v4i*)(Qh + (size_t)min(i, N - 1) * D + 32 * s + 16 * g);
     // ---- loop-invariant registers, set up before any K/V tile is in flight
-    const ExpConst c = make_exp_const(a);
+    const ExpConst c = make_exp_const(hc);
     constexpr bool SB = score_biased<D, BC, BIAS, NARROW, XM>();
     // Block of 0x80000000 that starts the accumulators (and, with biased scores, every score
     // block) at their offset.  With biased scores it is used in every tile: made opaque so that it
@@ -614,12 +621,12 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // ---- stage the weight table (L2-resident, shared by every workgroup of the launch): four
     //      16-byte pieces per thread in flight at a time
     if (XM == kExpTable) {
-        const int nch = tbytes / 16;
+        const int nch = hc.lut_bytes / 16;
         for (int ch0 = wg_tid; ch0 < nch; ch0 += 4 * wg_nthr) {
             v4i t[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (ch0 + u * wg_nthr < nch) t[u] = *(const v4i*)(a.lut + 16 * (ch0 + u * wg_nthr));
+                if (ch0 + u * wg_nthr < nch) t[u] = *(const v4i*)(hc.lut + 16 * (ch0 + u * wg_nthr));
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 if (ch0 + u * wg_nthr < nch) *(v4i*)(smem + 16 * (ch0 + u * wg_nthr)) = t[u];
@@ -662,8 +669,8 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
 #define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
     if (active)                                                                                              \
     process_tile<D, BC, BIAS, XM, SB, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,          \
-                                                     sV + (J_) * BC, VROW, NV_, a.lut_xp,                    \
-                                                     BIAS ? bias_row + (J_) * BC : nullptr, c, a.a_mul, li, g, zb)
+                                                     sV + (J_) * BC, VROW, NV_, hc.lut_xp,                   \
+                                                     BIAS ? bias_row + (J_) * BC : nullptr, c, hc.a_mul, li, g, zb)
     // Pipelined mode, around tile j: tile j+1 (loaded while tile j-1 was processed) goes to LDS and
     // the loads of tile j+2 are issued before the arithmetic of tile j; the barrier after it
     // publishes tile j+1, which every wavefront wrote long before.
@@ -742,7 +749,8 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         qreg[s] = v4i{0, 0, 0, 0};
         if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
     }
-    const ExpConst c = make_exp_const(a);
+    const QflashHeadConsts& hc = head_consts(a, bh);
+    const ExpConst c = make_exp_const(hc);
     v16i zb;   // starts the accumulators at their offset 2^31 in the first tile
 #pragma unroll
     for (int v = 0; v < 16; ++v) zb[v] = kAccBias;
@@ -769,11 +777,11 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         const int n_valid = min(BC, N - c0);
         const int32_t* brow = BIAS ? bias_row + c0 : nullptr;
         if (j == 0)
-            process_tile<D, BC, BIAS, kExpShift, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, a.a_mul, li, g, zb);
+            process_tile<D, BC, BIAS, kExpShift, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, hc.a_mul, li, g, zb);
         else if (n_valid == BC)
-            process_tile<D, BC, BIAS, kExpShift, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, 0, brow, c, a.a_mul, li, g, zb);
+            process_tile<D, BC, BIAS, kExpShift, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, 0, brow, c, hc.a_mul, li, g, zb);
         else
-            process_tile<D, BC, BIAS, kExpShift, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, a.a_mul, li, g, zb);
+            process_tile<D, BC, BIAS, kExpShift, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, hc.a_mul, li, g, zb);
     }
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
@@ -788,7 +796,7 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
 // and below -x_p.  Entries [n, n_padded) are 0 and never addressed.  Built by the same device
 // functions the arithmetic mode uses, so the two modes cannot disagree.
 __global__ __launch_bounds__(256) void qflash_build_table(uint8_t* tbl, int n, int n_padded, int x_p,
-                                                          const QflashKernelArgs a) {
+                                                          const QflashHeadConsts a) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n_padded) return;
     const ExpConst c = make_exp_const(a);
@@ -817,8 +825,8 @@ int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, 
 
 template <int D, int BC, bool BIAS, bool NARROW>
 int launch_mode(const QflashKernelArgs& a, size_t lds, int lds_limit, int threads, hipStream_t st) {
-    if (a.lut) return launch_resident<D, BC, BIAS, NARROW, kExpTable>(a, lds, lds_limit, threads, st);
-    if (a.x_shift == 0) return launch_resident<D, BC, BIAS, NARROW, kExpShift0>(a, lds, lds_limit, threads, st);
+    if (a.exp_mode == kExpTable) return launch_resident<D, BC, BIAS, NARROW, kExpTable>(a, lds, lds_limit, threads, st);
+    if (a.exp_mode == kExpShift0) return launch_resident<D, BC, BIAS, NARROW, kExpShift0>(a, lds, lds_limit, threads, st);
     return launch_resident<D, BC, BIAS, NARROW, kExpShift>(a, lds, lds_limit, threads, st);
 }
 
@@ -895,7 +903,7 @@ int qflash_table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds
     return resident_lds_bytes(a.N, d, a.heads_per_wg, table_bytes, budget) != 0;
 }
 
-int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashKernelArgs& a, void* stream) {
+int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashHeadConsts& a, void* stream) {
     hipLaunchKernelGGL(qflash_build_table, dim3((unsigned)((n_padded + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, tbl, n, n_padded, x_p, a);
     return (int)hipGetLastError();
@@ -903,7 +911,7 @@ int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const 
 
 int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.lut ? a.lut_bytes : 0, lds_limit) : 0;
+    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.exp_mode == kExpTable ? a.lut_bytes_max : 0, lds_limit) : 0;
     if (a.resident && lds == 0) return (int)hipErrorInvalidValue;
     const int threads = a.resident ? 64 * a.waves_per_head * a.heads_per_wg : kStreamThreads;
     if (d == 64 && kv_tile == 64) return launch_dbc<64, 64>(a, a.resident, lds, lds_limit, threads, st);

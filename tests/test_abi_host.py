@@ -82,6 +82,10 @@ def test_context_errors_without_gpu(lib):
                                 ctypes.byref(p), None) == qf.ERR["NULL"]
     assert lib.qflash_attention(bogus, one, one, one, one, None, 0, 0, 1, 1, 1, 64, 64,
                                 ctypes.byref(p), None) == qf.ERR["CTX"]
+    assert lib.qflash_attention_per_head(None, one, one, one, one, None, 0, 0, 1, 1, 1, 64, 64,
+                                         ctypes.byref(p), None) == qf.ERR["NULL"]
+    assert lib.qflash_attention_per_head(bogus, one, one, one, one, None, 0, 0, 1, 1, 1, 64, 64,
+                                         ctypes.byref(p), None) == qf.ERR["CTX"]
     h = ctypes.c_void_p()
     rc = lib.qflash_create(ctypes.byref(h), 9999)
     assert rc == qf.ERR["DEVICE"] and not h.value

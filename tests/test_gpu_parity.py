@@ -209,6 +209,89 @@ def test_table1_workloads(gpu, name):
         check(gpu, wl.Q, wl.K, wl.V, p, tile, bias=wl.bias, label=name)
 
 
+# ------------------------------------------------------------- per-head constants (Appendix C3)
+
+
+def run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=None):
+    torch, qf, ctx = gpu
+    dev = torch.device("cuda:0")
+    tQ, tK, tV = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (Q, K, V))
+    tO = torch.full(Q.shape, 0x55, dtype=torch.int8, device=dev)
+    tB = torch.from_numpy(np.ascontiguousarray(bias)).to(dev) if bias is not None else None
+    ctx.attention(tQ, tK, tV, tO, [lib_params(qf, p) for p in ps], tile, bias=tB)
+    torch.cuda.synchronize()
+    return tO.cpu().numpy()
+
+
+def check_per_head(gpu, Q, K, V, ps, tile, bias=None, label=""):
+    print("per-head case", label, Q.shape, "tile", tile, "bias", bias is not None, flush=True)
+    ref = oracle.qflash_attention(Q, K, V, ps, tile, bias=bias)
+    out = run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=bias)
+    bad = np.argwhere(out != ref)
+    assert bad.size == 0, "%s: %d mismatches, first at %s: gpu %d oracle %d" % (
+        label, len(bad), bad[0], out[tuple(bad[0])], ref[tuple(bad[0])])
+
+
+@pytest.mark.parametrize("shape,tile", [((2, 4, 197, 64), 64), ((3, 5, 49, 32), 64), ((1, 3, 300, 64), 128),
+                                        ((2, 6, 70, 32), 64), ((1, 2, 1200, 64), 64), ((1, 64, 40, 32), 64)])
+def test_per_head_constants(gpu, shape, tile):
+    """Heads with scales a factor 200 apart (some need x_shift > 0, so the launch mixes shifts),
+    every kernel family: one head per workgroup with and without tile-by-tile staging, several
+    windows per workgroup, the streamed kernel, the largest head count; with and without bias."""
+    from workloads import quantize_per_head
+    B, H, N, d = shape
+    rng = np.random.default_rng(900 + N + H)
+    gain = np.exp2(np.linspace(-2.5, 5.3, H))[None, :, None, None]
+    Qf = rng.standard_normal(shape) * gain
+    Kf = rng.standard_normal(shape) * gain
+    Vf = rng.standard_normal(shape)
+    (Q, sQ), (K, sK), (V, sV) = (quantize_per_head(x.astype(np.float32)) for x in (Qf, Kf, Vf))
+    ps = [oracle.derive_params(sQ[h], sK[h], d) for h in range(H)]
+    if H >= 4:
+        assert len({p.x_shift for p in ps}) > 1
+    check_per_head(gpu, Q, K, V, ps, tile, label="random")
+    bias = rng.integers(-3000, 3000, size=(2, H, N, N)).astype(np.int32)
+    bias[:, :, :, ::7] = EXCLUDED
+    bias[1, 0, 3, :] = EXCLUDED
+    check_per_head(gpu, Q, K, V, ps, tile, bias=bias, label="bias")
+
+
+def test_per_head_equal_constants_match_per_tensor_call(gpu):
+    wl = make_workload("a2_deit_s_b8")
+    p = oracle.derive_params(wl.sQ, wl.sK, wl.shape[-1])
+    a = run_gpu(gpu, wl.Q, wl.K, wl.V, p, 64)
+    b = run_gpu_per_head(gpu, wl.Q, wl.K, wl.V, [p] * wl.shape[1], 64)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["vit_b16_b64", "deit_b384_b32"])
+def test_per_head_workloads_full_size(gpu, name):
+    """The per-head variant of two benchmark workloads (heads of different range, one scale per
+    head), at full size, every byte."""
+    wl = make_workload(name, per_head=True)
+    H, d = wl.shape[1], wl.shape[3]
+    ps = [oracle.derive_params(wl.sQ[h], wl.sK[h], d) for h in range(H)]
+    check_per_head(gpu, wl.Q, wl.K, wl.V, ps, wl.kv_tiles[0], label=wl.name)
+
+
+def test_per_head_errors(gpu):
+    torch, qf, ctx = gpu
+    dev = torch.device("cuda:0")
+    p = qf.qflash_params_from_scales(0.02, 0.02, 0.02, 32)
+    q = torch.zeros((1, 65, 8, 32), dtype=torch.int8, device=dev)
+    with pytest.raises(qf.QFlashError) as e:
+        ctx.attention(q, q, q, torch.empty_like(q), [p] * 65, 64)
+    assert e.value.code == qf.ERR["SHAPE"]
+    q = torch.zeros((1, 2, 8, 32), dtype=torch.int8, device=dev)
+    p2 = qf.QFlashParams(*p.astuple())
+    p2.out_round = 1
+    with pytest.raises(qf.QFlashError) as e:
+        ctx.attention(q, q, q, torch.empty_like(q), [p, p2], 64)
+    assert e.value.code == qf.ERR["PARAM"]
+    with pytest.raises(ValueError):
+        ctx.attention(q, q, q, torch.empty_like(q), [p], 64)
+
+
 # ------------------------------------------------------------------------------ ABI behaviour
 
 
