@@ -11,6 +11,7 @@ Contents
 * ``shift_exp2`` etc.        the scalar building blocks of the C oracle, exposed for pins
 * ``fullrow_int_attention``  brute force: integer softmax over the whole row at once (NumPy)
 * ``float_attention``        exact softmax attention in float64 on dequantised inputs (NumPy)
+* ``dynamic_quantize``, ``qflash_attention_dynamic``  Eq. 1-2 on the fly in front of Algorithm 1
 """
 from .params import OracleParams, derive_params
 from .cbinding import (
@@ -31,7 +32,10 @@ from .bruteforce import (
     float_attention_ratio,
 )
 
+from .dynamic import dynamic_quantize, qflash_attention_dynamic
+
 __all__ = [
+    "dynamic_quantize", "qflash_attention_dynamic",
     "OracleParams", "derive_params", "build_oracle", "qflash_attention", "shift_exp2",
     "shift_exp2_quotient", "requant", "alpha16", "scale_release", "num_threads",
     "shift_exp2_np", "requant_np", "fullrow_int_attention", "float_attention",
