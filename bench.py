@@ -38,6 +38,10 @@ def main():
     ap.add_argument("--workload", default=None)
     ap.add_argument("--kv-tile", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dynamic", action="store_true",
+                    help="start from float32 Q, K, V: abs-max, scales, constants and quantisation on "
+                         "the GPU in front of the attention kernel (qflash_attention_dynamic); one "
+                         "step is the whole pipeline")
     ap.add_argument("--per-head", action="store_true",
                     help="per-head variant of the workload: heads of different range, one set of "
                          "integer constants per head (qflash_attention_per_head)")
@@ -71,18 +75,29 @@ def main():
 
     io_bytes = 4 * B * H * N * d                       # Q, K, V read once, O written once
     bias_bytes = wl.bias.nbytes if wl.bias is not None else 0
+    if args.dynamic:
+        # float32 Q, K, V read twice (abs-max, quantise), int8 copies written and read, O written
+        from workloads import make_float_qkv
+        floats = make_float_qkv(name)
+        io_bytes = (2 * 12 + 3 + 3 + 1) * B * H * N * d
     n_sets = max(1, -(-int(LLC_BYTES * 1.25) // io_bytes))
-    base = [torch.from_numpy(x).to(dev) for x in (wl.Q, wl.K, wl.V)]
+    src = floats if args.dynamic else (wl.Q, wl.K, wl.V)
+    base = [torch.from_numpy(x).to(dev) for x in src]
     sets = []
     for r in range(n_sets):
         q, k, v = (torch.roll(t, shifts=r, dims=0).contiguous() if r else t for t in base)
-        sets.append((q, k, v, torch.empty_like(q)))
+        sets.append((q, k, v, torch.empty(q.shape, dtype=torch.int8, device=dev)))
     bias = torch.from_numpy(wl.bias).to(dev) if wl.bias is not None else None
     ctx = qf.Context(0)
+    if args.dynamic:
+        ws = torch.empty(qf.qflash_dynamic_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=dev)
 
     def step(i):
         q, k, v, o = sets[i % len(sets)]
-        ctx.attention(q, k, v, o, params, tile, bias=bias)
+        if args.dynamic:
+            ctx.attention_dynamic(q, k, v, o, tile, ws)
+        else:
+            ctx.attention(q, k, v, o, params, tile, bias=bias)
 
     def timed(n_steps, rotate=True):
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -124,7 +139,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get("%s/kv%d" % (name, tile))
+            traffic = json.load(f).get("%s/kv%d%s" % (name, tile, "/dynamic" if args.dynamic else ""))
 
     def roof(bound, achieved, peak, unit):
         return {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
@@ -137,7 +152,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8/int32",
         "data": "synthetic",
         "config": {"workload": name, "B": B, "H": H, "N": N, "d": d, "kv_tile": tile,
-                   "bias": wl.bias is not None, "scales": "per_head" if args.per_head else "per_tensor",
+                   "bias": wl.bias is not None,
+                   "scales": "dynamic" if args.dynamic else "per_head" if args.per_head else "per_tensor",
                    "input_sets_rotated": len(sets)},
         "kernel_us_events": kern_s * 1e6,
         "hot_cache": {"kernel_us_events": ev_hot / args.steps * 1e6,
@@ -149,16 +165,26 @@ def main():
         "roofline_mfma": roof("mfma", ops / kern_s / 1e12, PEAK_MFMA_INT8_TOPS, "TOP/s"),
     }
 
+    if args.dynamic:
+        # the pipeline as a whole streams float32 tensors twice: the HBM roof is the one to quote
+        out["roofline"] = out["roofline_hbm"]
+
     if not args.no_cpu_baseline:
         import oracle
-        if args.per_head:
+        if args.dynamic:
+            t0 = time.perf_counter()
+            ref, _ = oracle.qflash_attention_dynamic(*floats, tile)
+            t_cpu, reps = time.perf_counter() - t0, 1
+            po = None
+        elif args.per_head:
             po = [oracle.derive_params(wl.sQ[h], wl.sK[h], d) for h in range(H)]
             assert all(a.astuple() == b.astuple() for a, b in zip(po, params))
         else:
             po = oracle.derive_params(wl.sQ, wl.sK, d)
             assert po.astuple() == params.astuple()
-        reps, t_cpu, ref = 0, 0.0, None
-        while t_cpu < 3.0 and reps < 20:               # a few full passes of the same workload
+        if not args.dynamic:
+            reps, t_cpu, ref = 0, 0.0, None
+        while not args.dynamic and t_cpu < 3.0 and reps < 20:   # a few full passes of the same workload
             t0 = time.perf_counter()
             ref = oracle.qflash_attention(wl.Q, wl.K, wl.V, po, tile, bias=wl.bias)
             t_cpu += time.perf_counter() - t0

@@ -14,6 +14,7 @@
 #ifndef QFLASH_H
 #define QFLASH_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -131,6 +132,46 @@ int qflash_attention_per_head(qflash_ctx* ctx,
                               const int32_t* bias, int bias_B, int bias_H,
                               int B, int H, int N, int d, int kv_tile,
                               const qflash_params* p /* host, H entries */, void* hip_stream);
+
+/*
+ * Dynamic quantisation (Section 5, evaluation set-up: activation scales computed on the fly;
+ * Eq. 1-2 with b = 8) in front of the same pass, entirely on the GPU and without waiting for it:
+ * per-tensor abs-max of the float32 tensors Qf, Kf, Vf, scales s_X = max|X| / 127, quantisation
+ * X_hat = clip(rint(X * r), -127, 127) with r = float32(127) / max|X| (one float32 multiplication
+ * per element, round half to even), derivation of the integer constants from s_Q and s_K exactly
+ * as qflash_params_from_scales does, then Algorithm 1.  An all-zero tensor gets scale 1.
+ *
+ *   Qf, Kf, Vf  device, float32, [B,H,N,d] contiguous, 16-byte aligned, finite values; read only.
+ *   O           device, int8, [B,H,N,d]; scale s_V as reported in *info.
+ *   info        device or NULL; receives the scales, the constants used and a status: QFLASH_OK,
+ *               or QFLASH_ERR_PARAM when the scales fall outside the supported window (O is then
+ *               unspecified; nothing out of bounds is touched).
+ *   workspace   device scratch of at least qflash_dynamic_workspace_bytes(B,H,N,d) bytes, 16-byte
+ *               aligned, caller-owned; it holds the int8 copies of Q, K, V among other things and
+ *               must stay untouched until the stream has executed the work.  The call allocates
+ *               nothing.
+ *   out_round, kv_tile, hip_stream  as for qflash_attention.  No bias in this entry point (an
+ *               integer bias is expressed in a score unit that is only known on the GPU here).
+ * The weights are always computed arithmetically (a table would have to be sized by constants
+ * the host does not know).
+ * Errors: CTX, NULL, SHAPE (also: workspace too small), TILE, PARAM (out_round), ALIGN, DEVICE,
+ * LAUNCH.
+ */
+typedef struct {
+    double sQ, sK, sV;       /* Eq. 1: max|X| / 127                                             */
+    qflash_params params;    /* the constants the attention kernel used                         */
+    int32_t status;          /* QFLASH_OK or QFLASH_ERR_PARAM                                   */
+    int32_t reserved;
+} qflash_dynamic_info;
+
+size_t qflash_dynamic_workspace_bytes(int B, int H, int N, int d);
+
+int qflash_attention_dynamic(qflash_ctx* ctx,
+                             const float* Qf, const float* Kf, const float* Vf, int8_t* O,
+                             int B, int H, int N, int d, int kv_tile, int out_round,
+                             qflash_dynamic_info* info /* device or NULL */,
+                             void* workspace /* device */, size_t workspace_bytes,
+                             void* hip_stream);
 
 /*
  * Destroy a context.  NULL is accepted (returns QFLASH_OK).  Destroying a context twice, or a

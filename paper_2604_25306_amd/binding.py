@@ -15,7 +15,8 @@ ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, 
        "CTX": -7, "ALIGN": -8}
 
 EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
-           "qflash_attention_per_head", "qflash_destroy", "qflash_strerror"]
+           "qflash_attention_per_head", "qflash_dynamic_workspace_bytes", "qflash_attention_dynamic",
+           "qflash_destroy", "qflash_strerror"]
 
 MAX_PARAM_HEADS = 64
 
@@ -40,6 +41,12 @@ class QFlashParams(ctypes.Structure):
         return "QFlashParams(%s)" % ", ".join("%s=%d" % (n, getattr(self, n)) for n, _ in self._fields_)
 
 
+class DynamicInfo(ctypes.Structure):
+    """Mirror of ``qflash_dynamic_info`` (what the dynamic entry point reports, in device memory)."""
+    _fields_ = [("sQ", ctypes.c_double), ("sK", ctypes.c_double), ("sV", ctypes.c_double),
+                ("params", QFlashParams), ("status", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -61,6 +68,11 @@ def load_library():
         lib.qflash_create.argtypes = [ctypes.POINTER(vp), ci]
         lib.qflash_attention.restype = ci
         lib.qflash_attention_per_head.restype = ci
+        lib.qflash_dynamic_workspace_bytes.restype = ctypes.c_size_t
+        lib.qflash_dynamic_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        lib.qflash_attention_dynamic.restype = ci
+        lib.qflash_attention_dynamic.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp,
+                                                 ctypes.c_size_t, vp]
         lib.qflash_attention_per_head.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
         lib.qflash_attention.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
         lib.qflash_configure.restype = ci
@@ -156,6 +168,38 @@ def qflash_attention_per_head(ctx: int, Q, K, V, O, params, kv_tile: int, bias=N
         raise QFlashError(rc, "qflash_attention_per_head")
 
 
+def qflash_dynamic_workspace_bytes(B: int, H: int, N: int, d: int) -> int:
+    return int(load_library().qflash_dynamic_workspace_bytes(int(B), int(H), int(N), int(d)))
+
+
+def qflash_attention_dynamic(ctx: int, Qf, Kf, Vf, O, kv_tile: int, workspace, info=None,
+                             out_round: int = 0, stream: Optional[int] = None) -> None:
+    """Quantise float32 CUDA tensors Qf, Kf, Vf [B,H,N,d] on the GPU and run the forward pass.
+    ``workspace``: uint8 CUDA tensor of at least ``qflash_dynamic_workspace_bytes`` bytes;
+    ``info``: None or a uint8 CUDA tensor of ``ctypes.sizeof(DynamicInfo)`` bytes."""
+    import torch
+    for name, t in (("Qf", Qf), ("Kf", Kf), ("Vf", Vf)):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4 \
+                or t.shape != Qf.shape:
+            raise ValueError("%s must be a contiguous float32 CUDA tensor [B,H,N,d]" % name)
+    if O.dtype != torch.int8 or not O.is_cuda or not O.is_contiguous() or O.shape != Qf.shape:
+        raise ValueError("O must be a contiguous int8 CUDA tensor [B,H,N,d]")
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 CUDA tensor")
+    if info is not None and (info.dtype != torch.uint8 or not info.is_cuda
+                             or info.numel() < ctypes.sizeof(DynamicInfo)):
+        raise ValueError("info must be a uint8 CUDA tensor of sizeof(DynamicInfo) bytes")
+    B, H, N, d = Qf.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(Qf.device).cuda_stream
+    rc = load_library().qflash_attention_dynamic(
+        ctypes.c_void_p(ctx), _ptr(Qf), _ptr(Kf), _ptr(Vf), _ptr(O), int(B), int(H), int(N), int(d),
+        int(kv_tile), int(out_round), _ptr(info), _ptr(workspace), int(workspace.numel()),
+        ctypes.c_void_p(stream))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_attention_dynamic")
+
+
 class Context:
     """RAII wrapper: ``with Context(0) as ctx: ctx.attention(...)``."""
 
@@ -171,6 +215,9 @@ class Context:
             qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
         else:
             qflash_attention_per_head(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
+
+    def attention_dynamic(self, Qf, Kf, Vf, O, kv_tile, workspace, info=None, out_round=0, stream=None):
+        qflash_attention_dynamic(self.handle, Qf, Kf, Vf, O, kv_tile, workspace, info, out_round, stream)
 
     def close(self):
         if self.handle is not None:

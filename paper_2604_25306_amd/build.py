@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqflash.so")
-SOURCES = ["qflash_api.cpp", "qflash_kernels.hip"]
+SOURCES = ["qflash_api.cpp", "qflash_kernels.hip", "qflash_dynamic.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

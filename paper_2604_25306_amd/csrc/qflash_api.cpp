@@ -12,6 +12,7 @@
 
 #include "qflash.h"
 #include "qflash_internal.h"
+#include "qflash_derive.h"
 
 // One immutable weight table.  A slot is written once (by a kernel enqueued on `stream`) and only
 // ever used by launches on that same stream, so stream order alone makes it safe; it is never
@@ -42,33 +43,6 @@ std::set<const qflash_ctx*>& live_contexts() {
     return s;
 }
 
-constexpr int kXShiftMax = 13;
-constexpr int kSInvMin = 1 << 10;
-constexpr int kSInvMax = 1 << 18;  // exclusive
-
-int64_t round_half_up(double x) { return (int64_t)std::floor(x + 0.5); }
-
-// Range and consistency checks that make the 32-bit kernel arithmetic exact (see the comments on
-// x_floor in qflash_internal.h and on shift_exp2 in the kernel source).
-bool params_ok(const qflash_params& p) {
-    if (p.x_shift < 0 || p.x_shift > kXShiftMax) return false;
-    if (p.s_inv < kSInvMin || p.s_inv >= kSInvMax) return false;
-    if (p.exp_shift != 32) return false;
-    if (p.exp_mul >= 0 || p.exp_mul <= -(1 << 23)) return false;
-    // M * s_inv must be -2^32 to within 0.1 %: both come from the same real scale.
-    const int64_t prod = (int64_t)p.exp_mul * (int64_t)p.s_inv + ((int64_t)1 << 32);
-    if (prod > ((int64_t)1 << 32) / 1000 || prod < -(((int64_t)1 << 32) / 1000)) return false;
-    // the kernel multiplies by p_mul << (24 - p_shift), a 24-bit operand, so that P lands in byte 3
-    if (p.p_shift < 8 || p.p_shift > 24 || p.p_mul < 1 || ((int64_t)p.p_mul << (24 - p.p_shift)) >= (1 << 23)) return false;
-    // 1.0 (= s_inv) must requantise to at most 127 so that P fits a signed byte.
-    if ((int64_t)p.s_inv * p.p_mul >= ((int64_t)128 << p.p_shift)) return false;
-    if (p.a_mul < 1 || (int64_t)p.s_inv * p.a_mul >= ((int64_t)1 << 31)) return false;
-    // alpha = 1.0 must map to exactly 2^16 (identity), i.e. s_inv * a_mul >= 2^30.
-    if ((int64_t)p.s_inv * p.a_mul < ((int64_t)1 << 30)) return false;
-    if (p.out_round != 0 && p.out_round != 1) return false;
-    return true;
-}
-
 }  // namespace
 
 extern "C" int qflash_params_from_scales(double sQ, double sK, double sV, int d, qflash_params* out) {
@@ -77,36 +51,7 @@ extern "C" int qflash_params_from_scales(double sQ, double sK, double sV, int d,
     if (!(sQ > 0.0) || !(sK > 0.0) || !(sV > 0.0) || !std::isfinite(sQ) || !std::isfinite(sK) ||
         !std::isfinite(sV))
         return QFLASH_ERR_PARAM;
-    // s = sQ * sK * d^(-1/2) * log2(e), evaluated left to right in double (Algorithm 1, Require).
-    const double log2e = 1.4426950408889634;
-    const double s = ((sQ * sK) / std::sqrt((double)d)) * log2e;
-    if (!(s > 0.0) || !std::isfinite(s)) return QFLASH_ERR_PARAM;
-    int k = 0;
-    while (round_half_up(std::ldexp(1.0, k) / s) < kSInvMin) {
-        if (++k > kXShiftMax) return QFLASH_ERR_PARAM;
-    }
-    const double sk = s / std::ldexp(1.0, k);
-    const int64_t s_inv = round_half_up(1.0 / sk);                 // Algorithm 2: round(1/s)
-    if (s_inv < kSInvMin || s_inv >= kSInvMax) return QFLASH_ERR_PARAM;
-    const int64_t m = round_half_up(-sk * 4294967296.0);           // Algorithm 2: round(-s * 2^N)
-    // Eq. 9: n = floor(log2(127/s_inv)) < 0, found with integers: 2^n <= 127/s_inv < 2^(n+1).
-    int e = 0;
-    while ((int64_t)127 << e < s_inv) ++e;
-    const int r = 8 + e;                                           // r = b - n, b = 8
-    const int64_t m_r = (2 * ((int64_t)127 << r) + s_inv) / (2 * s_inv);   // Eq. 10: round(127/s_inv*2^r)
-    const int64_t a_mul = (((int64_t)1 << 30) + s_inv - 1) / s_inv;
-    qflash_params p;
-    p.x_shift = k;
-    p.s_inv = (int32_t)s_inv;
-    p.exp_mul = (int32_t)m;
-    p.exp_shift = 32;
-    p.p_mul = (int32_t)m_r;
-    p.p_shift = r;
-    p.a_mul = (int32_t)a_mul;
-    p.out_round = 0;
-    if (!params_ok(p)) return QFLASH_ERR_PARAM;
-    *out = p;
-    return QFLASH_OK;
+    return qflash_derive_params(sQ, sK, std::sqrt((double)d), out);
 }
 
 extern "C" int qflash_create(qflash_ctx** out, int device_id) {
@@ -176,24 +121,13 @@ extern "C" int qflash_configure(qflash_ctx* ctx, int key, int value) {
 
 namespace {
 
-// Clamp point of the exponent: smallest multiple of 2^-k at or below -20.5 octaves.  Above it
-// q <= 28 and every intermediate fits 24/32 bits; at and below it the numerator of Algorithm 2
-// (< 2^20) is shifted right by >= 20, so the exact result is 0.  Returns false if the constants
-// put it beyond 28.5 octaves.
-bool fill_head_consts(const qflash_params& p, QflashHeadConsts* h) {
-    h->x_shift = p.x_shift; h->s_inv = p.s_inv; h->exp_mul = p.exp_mul;
-    h->p_mul = p.p_mul; h->p_shift = p.p_shift; h->a_mul = p.a_mul;
-    const int64_t x0 = (41 * (int64_t)p.s_inv + ((int64_t)2 << p.x_shift) - 1) >> (p.x_shift + 1);
-    if ((x0 << p.x_shift) * 2 > 57 * (int64_t)p.s_inv) return false;
-    h->x_floor = (int)-x0;
-    h->lut = nullptr; h->lut_bytes = 0; h->lut_xp = 0;
-    return true;
-}
-
 // Shared by the per-tensor and the per-head entry points: n_p = 1 (p[0] serves every head) or H.
+// hc_dev != nullptr: the constants are computed on the GPU (dynamic quantisation); p is then not
+// used and out_round_dev gives the rounding mode.
 int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
                    const int32_t* bias, int bias_B, int bias_H, int B, int H, int N, int d, int kv_tile,
-                   const qflash_params* p, bool per_head, void* hip_stream) {
+                   const qflash_params* p, bool per_head, void* hip_stream,
+                   const QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0) {
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit;
     {
@@ -202,7 +136,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         device = ctx->device;
         lds_limit = ctx->lds_limit;
     }
-    if (!Q || !K || !V || !O || !p) return QFLASH_ERR_NULL;
+    if (!Q || !K || !V || !O || (!p && !hc_dev)) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
     if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
     if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
@@ -212,9 +146,9 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
     }
     if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
-    const int n_p = per_head ? H : 1;
+    const int n_p = hc_dev ? 0 : per_head ? H : 1;
     for (int h = 0; h < n_p; ++h) {
-        if (!params_ok(p[h])) return QFLASH_ERR_PARAM;
+        if (!qflash_params_ok(p[h])) return QFLASH_ERR_PARAM;
         if (p[h].out_round != p[0].out_round) return QFLASH_ERR_PARAM;   // one rounding mode per call
     }
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
@@ -227,11 +161,12 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.bias_B = bias ? bias_B : 1;
     a.bias_H = bias ? bias_H : 1;
     a.B = B; a.H = H; a.N = N;
-    a.out_round = p[0].out_round;
+    a.out_round = hc_dev ? out_round_dev : p[0].out_round;
     a.per_head = per_head ? 1 : 0;
-    bool all_k0 = true;
+    a.hc_dev = hc_dev;
+    bool all_k0 = hc_dev == nullptr;
     for (int h = 0; h < n_p; ++h) {
-        if (!fill_head_consts(p[h], &a.hc[h])) return QFLASH_ERR_PARAM;
+        if (!qflash_fill_head_consts(p[h], &a.hc[h])) return QFLASH_ERR_PARAM;
         all_k0 = all_k0 && p[h].x_shift == 0;
     }
     a.exp_mode = all_k0 ? 1 : 0;
@@ -251,7 +186,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     int rc = 0;
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        bool ok = ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1);
+        bool ok = !hc_dev && ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1);
         int xp[kQflashMaxParamHeads], np_[kQflashMaxParamHeads], max_bytes = 0;
         for (int h = 0; ok && h < n_p; ++h) {
             // weight is 0 at and below -8 octaves: x_p = ceil(8 s_inv / 2^k)
@@ -311,6 +246,61 @@ extern "C" int qflash_attention_per_head(qflash_ctx* ctx, const int8_t* Q, const
                                          int H, int N, int d, int kv_tile, const qflash_params* p,
                                          void* hip_stream) {
     return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, true, hip_stream);
+}
+
+// Workspace layout of the dynamic entry point: [int8 Q | int8 K | int8 V | constants | abs-max scratch]
+namespace {
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+}
+
+extern "C" size_t qflash_dynamic_workspace_bytes(int B, int H, int N, int d) {
+    if (B < 1 || H < 1 || N < 1 || d < 1) return 0;
+    const size_t n = (size_t)B * H * N * d;
+    return 3 * align256(n) + align256(sizeof(QflashHeadConsts)) +
+           align256(sizeof(float) * (4 + 3 * (size_t)qflash_dynamic_partials((long long)n)));
+}
+
+extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const float* Kf, const float* Vf,
+                                        int8_t* O, int B, int H, int N, int d, int kv_tile, int out_round,
+                                        qflash_dynamic_info* info, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream) {
+    if (!ctx) return QFLASH_ERR_NULL;
+    int device;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+        device = ctx->device;
+    }
+    if (!Qf || !Kf || !Vf || !O || !workspace) return QFLASH_ERR_NULL;
+    if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
+    if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
+    if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+    if (workspace_bytes < qflash_dynamic_workspace_bytes(B, H, N, d)) return QFLASH_ERR_SHAPE;
+    if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
+    if (out_round != 0 && out_round != 1) return QFLASH_ERR_PARAM;
+    if (((uintptr_t)Qf | (uintptr_t)Kf | (uintptr_t)Vf | (uintptr_t)O | (uintptr_t)workspace) & 15u) return QFLASH_ERR_ALIGN;
+    if (info && ((uintptr_t)info & 7u)) return QFLASH_ERR_ALIGN;
+
+    const size_t n = (size_t)B * H * N * d;        // a multiple of 32
+    int8_t* ws = (int8_t*)workspace;
+    int8_t* Qo = ws;
+    int8_t* Ko = Qo + align256(n);
+    int8_t* Vo = Ko + align256(n);
+    QflashHeadConsts* hc_dev = (QflashHeadConsts*)(Vo + align256(n));
+    float* scratch = (float*)((int8_t*)hc_dev + align256(sizeof(QflashHeadConsts)));
+
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }
+    if (cur != device && hipSetDevice(device) != hipSuccess) {
+        (void)hipGetLastError();
+        return QFLASH_ERR_DEVICE;
+    }
+    int rc = qflash_launch_dynamic_front(Qf, Kf, Vf, Qo, Ko, Vo, (long long)n, std::sqrt((double)d), out_round,
+                                         scratch, hc_dev, info, hip_stream);
+    if (cur != device) (void)hipSetDevice(cur);
+    if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
+    return attention_impl(ctx, Qo, Ko, Vo, O, nullptr, 0, 0, B, H, N, d, kv_tile, nullptr, false, hip_stream,
+                          hc_dev, out_round);
 }
 
 extern "C" const char* qflash_strerror(int code) {

@@ -1,0 +1,138 @@
+// Dynamic per-tensor quantisation in front of the attention kernel (Eq. 1-2 evaluated on the fly,
+// as in the paper's evaluation set-up), entirely on the GPU: no value ever travels to the host.
+//
+//   1. abs-max    max |x| over each of Q, K, V (float32): one partial maximum per workgroup (a
+//                 maximum is exact in any order, so the result does not depend on the grid)
+//   2. quantise   every workgroup finishes the reduction of its tensor; one of them also derives the
+//                 scales s_X = max|X| / 127 (double) and, from s_Q and s_K, every integer constant of
+//                 the attention kernel -- the same routine the host entry point uses.  Then
+//                 x_hat = clip(rint(x * r), -127, 127), r = float32(127) / max|x|: one float32
+//                 division per tensor, one float32 multiplication and one round-half-to-even per
+//                 element (the precision the rounding decision is defined in)
+//   3. attention  the usual kernel, reading its constants from the device structure of step 2
+//
+// Steps 1 and 2 stream the float32 tensors once each and are bound by HBM: 12 B read in step 1
+// and 12 B read + 3 B written in step 2 per (q, k, v) element triple.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qflash.h"
+#include "qflash_internal.h"
+#include "qflash_derive.h"
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// grid.y = tensor (0: Q, 1: K, 2: V); n4 = elements / 4.  Each workgroup leaves its maximum in
+// partial[tensor * gridDim.x + workgroup]: atomics on three words would serialise at the L2.
+__global__ __launch_bounds__(256) void qflash_dyn_absmax(const float* q, const float* k, const float* v,
+                                                        long long n4, float* partial) {
+    __shared__ float wmax[4];
+    const float* x = blockIdx.y == 0 ? q : blockIdx.y == 1 ? k : v;
+    float m = 0.0f;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
+        const v4f t = *(const v4f*)(x + 4 * i);
+        m = fmaxf(fmaxf(m, fabsf(t[0])), fmaxf(fabsf(t[1]), fmaxf(fabsf(t[2]), fabsf(t[3]))));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial[blockIdx.y * gridDim.x + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+}
+
+// Maximum over n_partial values by one workgroup of 256 threads; every thread gets the result.
+__device__ __forceinline__ float wg_max(const float* partial, int n_partial, float* wmax /* 4 floats of LDS */) {
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < n_partial; i += 256) m = fmaxf(m, partial[i]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    __syncthreads();                       // wmax may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    return fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+}
+
+// Scales and constants from the three maxima (one thread).
+__device__ void derive_on_device(const float am[3], double sqrt_d, int out_round, QflashHeadConsts* hc,
+                                 qflash_dynamic_info* info) {
+    double s[3];
+    for (int t = 0; t < 3; ++t) s[t] = am[t] == 0.0f ? 1.0 : (double)am[t] / 127.0;   // all-zero tensor: scale 1
+    qflash_params p;
+    int status = qflash_derive_params(s[0], s[1], sqrt_d, &p);
+    if (status == QFLASH_OK) {
+        p.out_round = out_round;
+        if (!qflash_fill_head_consts(p, hc)) status = QFLASH_ERR_PARAM;
+    }
+    if (status != QFLASH_OK) {
+        // Scales outside the supported window: keep the attention kernel on safe constants (those
+        // of a mid-range scale) so that it runs without touching anything it should not; its output
+        // is then meaningless and the status says so.
+        (void)qflash_derive_params(0.03, 0.03, sqrt_d, &p);
+        p.out_round = out_round;
+        (void)qflash_fill_head_consts(p, hc);
+    }
+    if (info) {
+        info->sQ = s[0]; info->sK = s[1]; info->sV = s[2];
+        info->params = p;
+        info->status = status;
+    }
+}
+
+// grid.y = tensor; 4 elements per thread and iteration: 16 B in, 4 B out.  Every workgroup first
+// finishes the abs-max reduction of its tensor from the per-workgroup partial maxima (a few KB,
+// L2-resident); workgroup (0, 0) also does so for the other two tensors and derives the scales and
+// constants for the attention kernel that follows on the stream.
+__global__ __launch_bounds__(256) void qflash_dyn_quantize(const float* q, const float* k, const float* v,
+                                                          int8_t* qo, int8_t* ko, int8_t* vo, long long n4,
+                                                          const float* partial, int n_partial, double sqrt_d,
+                                                          int out_round, QflashHeadConsts* hc,
+                                                          qflash_dynamic_info* info) {
+    __shared__ float wmax[4];
+    const float* x = blockIdx.y == 0 ? q : blockIdx.y == 1 ? k : v;
+    int8_t* y = blockIdx.y == 0 ? qo : blockIdx.y == 1 ? ko : vo;
+    const float am = wg_max(partial + blockIdx.y * n_partial, n_partial, wmax);
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        float a3[3];
+        a3[0] = am;
+        a3[1] = wg_max(partial + n_partial, n_partial, wmax);
+        a3[2] = wg_max(partial + 2 * n_partial, n_partial, wmax);
+        if (threadIdx.x == 0) derive_on_device(a3, sqrt_d, out_round, hc, info);
+    }
+    const float r = am == 0.0f ? 0.0f : __fdiv_rn(127.0f, am);
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
+        const v4f t = *(const v4f*)(x + 4 * i);
+        unsigned w = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float z = fminf(fmaxf(rintf(__fmul_rn(t[e], r)), -127.0f), 127.0f);
+            w |= ((unsigned)(int)z & 0xffu) << (8 * e);
+        }
+        *(unsigned*)(y + 4 * i) = w;
+    }
+}
+
+}  // namespace
+
+int qflash_dynamic_partials(long long n) {
+    // enough workgroups to keep every HBM channel busy; each streams a contiguous-stride share
+    long long wgs = (n / 4 + 255) / 256;
+    if (wgs > 2048) wgs = 2048;
+    if (wgs < 1) wgs = 1;
+    return (int)wgs;
+}
+
+int qflash_launch_dynamic_front(const float* Qf, const float* Kf, const float* Vf, int8_t* Qo, int8_t* Ko, int8_t* Vo,
+                                long long n, double sqrt_d, int out_round, float* scratch,
+                                QflashHeadConsts* hc_dev, qflash_dynamic_info* info, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    const long long n4 = n / 4;
+    const int wgs = qflash_dynamic_partials(n);
+    float* partial = scratch;         // 3 * wgs words
+    hipLaunchKernelGGL(qflash_dyn_absmax, dim3((unsigned)wgs, 3), dim3(256), 0, st, Qf, Kf, Vf, n4, partial);
+    hipLaunchKernelGGL(qflash_dyn_quantize, dim3((unsigned)wgs, 3), dim3(256), 0, st, Qf, Kf, Vf, Qo, Ko, Vo, n4,
+                       (const float*)partial, wgs, sqrt_d, out_round, hc_dev, info);
+    return (int)hipGetLastError();
+}

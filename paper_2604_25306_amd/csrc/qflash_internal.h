@@ -2,6 +2,8 @@
 #pragma once
 #include <stdint.h>
 
+#include "qflash.h"
+
 // Integer constants of Algorithm 1 / 2 for one head, or for the whole tensor (see qflash_params).
 struct QflashHeadConsts {
     int x_shift, s_inv, exp_mul, p_mul, p_shift, a_mul;
@@ -38,6 +40,9 @@ struct QflashKernelArgs {
     int exp_mode;
     int lut_bytes_max;       // LDS bytes reserved for the table: the largest of all heads
     int per_head;            // 0: hc[0] serves every head; 1: head h uses hc[h] (H <= kQflashMaxParamHeads)
+    // Constants computed on the GPU (dynamic quantisation): if set, the kernel reads this device
+    // structure instead of hc[]; exp_mode is then 0 (the host does not know the constants).
+    const QflashHeadConsts* hc_dev;
     QflashHeadConsts hc[kQflashMaxParamHeads];
 };
 
@@ -55,3 +60,11 @@ int qflash_table_fits(const QflashKernelArgs& args, int d, int table_bytes, int 
 
 // Enqueue the kernel that fills a weight table of n entries (n_padded bytes) for the constants hc.
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashHeadConsts& hc, void* stream);
+
+// Enqueue the front end of the dynamic pipeline: abs-max of the three float32 tensors of n elements
+// each (n a multiple of 4), derivation of the scales and constants into *hc_dev (and *info if not
+// null), quantisation into Qo, Ko, Vo.  scratch: 3 * qflash_dynamic_partials(n) device floats.
+int qflash_dynamic_partials(long long n);
+int qflash_launch_dynamic_front(const float* Qf, const float* Kf, const float* Vf, int8_t* Qo, int8_t* Ko, int8_t* Vo,
+                                long long n, double sqrt_d, int out_round, float* scratch,
+                                QflashHeadConsts* hc_dev, qflash_dynamic_info* info, void* stream);

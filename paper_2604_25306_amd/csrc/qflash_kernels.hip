@@ -441,7 +441,9 @@ __device__ __forceinline__ ExpConst make_exp_const(const QflashHeadConsts& h) {
 
 // Constants of the head that (batch, head) pair bh belongs to.  bh is uniform over the wavefront,
 // so these are scalar loads from the kernel arguments.
-__device__ __forceinline__ const QflashHeadConsts& head_consts(const QflashKernelArgs& a, int bh) {
+// With dynamic quantisation they were computed on the GPU and live in device memory.
+__device__ __forceinline__ QflashHeadConsts head_consts(const QflashKernelArgs& a, int bh) {
+    if (a.hc_dev) return *a.hc_dev;
     return a.hc[a.per_head ? bh % a.H : 0];
 }
 
@@ -527,7 +529,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int qt = a.heads_per_wg > 1 ? 0 : unit % a.n_qtiles;
     const int bh = a.heads_per_wg > 1 ? unit * a.heads_per_wg + sub : unit / a.n_qtiles;
     const bool pair_valid = bh < a.B * a.H;
-    const QflashHeadConsts& hc = head_consts(a, pair_valid ? bh : 0);
+    const QflashHeadConsts hc = head_consts(a, pair_valid ? bh : 0);
     const int row0 = qt * a.rows_per_wg + (wave - sub * a.waves_per_head) * 32;
     const int i = row0 + li;
 
@@ -749,7 +751,7 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         qreg[s] = v4i{0, 0, 0, 0};
         if (i < N) qreg[s] = *(const v4i*)(Qh + (size_t)i * D + 32 * s + 16 * g);
     }
-    const QflashHeadConsts& hc = head_consts(a, bh);
+    const QflashHeadConsts hc = head_consts(a, bh);
     const ExpConst c = make_exp_const(hc);
     v16i zb;   // starts the accumulators at their offset 2^31 in the first tile
 #pragma unroll

@@ -292,6 +292,89 @@ def test_per_head_errors(gpu):
         ctx.attention(q, q, q, torch.empty_like(q), [p], 64)
 
 
+# ------------------------------------------------- dynamic quantisation in front of the kernel
+
+
+def run_dynamic(gpu, Qf, Kf, Vf, tile, out_round=0):
+    torch, qf, ctx = gpu
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev) for x in (Qf, Kf, Vf))
+    tO = torch.full(Qf.shape, 0x55, dtype=torch.int8, device=dev)
+    ws = torch.empty(qf.qflash_dynamic_workspace_bytes(*Qf.shape), dtype=torch.uint8, device=dev)
+    info = torch.zeros(ctypes.sizeof(qf.DynamicInfo), dtype=torch.uint8, device=dev)
+    ctx.attention_dynamic(tq, tk, tv, tO, tile, ws, info=info, out_round=out_round)
+    torch.cuda.synchronize()
+    inf = qf.DynamicInfo.from_buffer_copy(info.cpu().numpy().tobytes())
+    n = Qf.size
+    a256 = lambda x: (x + 255) & ~255
+    wsn = ws.cpu().numpy()
+    qkv = [wsn[i * a256(n): i * a256(n) + n].view(np.int8).reshape(Qf.shape) for i in range(3)]
+    return tO.cpu().numpy(), inf, qkv
+
+
+@pytest.mark.parametrize("shape,tile,gains", [((2, 3, 197, 64), 64, (1.0, 1.0, 1.0)), ((3, 4, 49, 32), 64, (0.3, 2.0, 1e-3)),
+                                              ((1, 2, 577, 64), 128, (40.0, 40.0, 5.0)), ((1, 1, 1, 32), 64, (1.0, 1.0, 1.0)),
+                                              ((1, 2, 1100, 64), 64, (1.5, 1.5, 1.0))])
+def test_dynamic_quantisation_pipeline(gpu, shape, tile, gains):
+    """Scales, quantised tensors, derived constants and the attention output all equal the oracle's
+    (float32 rounding decisions included); a heavy-gain case needs x_shift > 0 on the GPU."""
+    rng = np.random.default_rng(4000 + shape[2])
+    Qf, Kf, Vf = ((rng.standard_normal(shape) * g).astype(np.float32) for g in gains)
+    for out_round in (0, 1):
+        ref, rinfo = oracle.qflash_attention_dynamic(Qf, Kf, Vf, tile, out_round=out_round)
+        out, inf, qkv = run_dynamic(gpu, Qf, Kf, Vf, tile, out_round=out_round)
+        assert inf.status == 0
+        assert (inf.sQ, inf.sK, inf.sV) == (rinfo["sQ"], rinfo["sK"], rinfo["sV"])
+        assert inf.params.astuple() == rinfo["params"].astuple()
+        for name, got in zip("QKV", qkv):
+            assert np.array_equal(got, rinfo[name]), name
+        assert np.array_equal(out, ref)
+    if gains[0] >= 40.0:
+        assert inf.params.x_shift > 0
+
+
+def test_dynamic_degenerate_and_out_of_window(gpu):
+    torch, qf, ctx = gpu
+    shape = (1, 2, 40, 32)
+    rng = np.random.default_rng(5)
+    Kf, Vf = (rng.standard_normal(shape).astype(np.float32) for _ in range(2))
+    # all-zero Q: scale 1, uniform weights
+    ref, rinfo = oracle.qflash_attention_dynamic(np.zeros(shape, np.float32), Kf, Vf, 64)
+    out, inf, _ = run_dynamic(gpu, np.zeros(shape, np.float32), Kf, Vf, 64)
+    assert inf.status == 0 and inf.sQ == 1.0 and np.array_equal(out, ref)
+    # scales far too fine for the integer exponent: reported, nothing crashes
+    with pytest.raises(ValueError):
+        oracle.qflash_attention_dynamic(Kf * 1e-6, Kf * 1e-6, Vf, 64)
+    out, inf, _ = run_dynamic(gpu, Kf * 1e-6, Kf * 1e-6, Vf, 64)
+    assert inf.status == qf.ERR["PARAM"]
+    # argument errors
+    dev = torch.device("cuda:0")
+    t = torch.zeros(shape, dtype=torch.float32, device=dev)
+    o = torch.zeros(shape, dtype=torch.int8, device=dev)
+    small = torch.empty(64, dtype=torch.uint8, device=dev)
+    with pytest.raises(qf.QFlashError) as e:
+        ctx.attention_dynamic(t, t, t, o, 64, small)
+    assert e.value.code == qf.ERR["SHAPE"]
+    ws = torch.empty(qf.qflash_dynamic_workspace_bytes(*shape), dtype=torch.uint8, device=dev)
+    with pytest.raises(qf.QFlashError) as e:
+        ctx.attention_dynamic(t, t, t, o, 64, ws, out_round=2)
+    assert e.value.code == qf.ERR["PARAM"]
+    with pytest.raises(qf.QFlashError) as e:
+        ctx.attention_dynamic(t, t, t, o, 96, ws)
+    assert e.value.code == qf.ERR["TILE"]
+
+
+def test_dynamic_headline_shape_full_size(gpu):
+    """ViT-B/16 B=64 from float32 activations, every output byte."""
+    rng = np.random.default_rng(4242)
+    shape = (64, 12, 197, 64)
+    Qf, Kf, Vf = (rng.standard_normal(shape, dtype=np.float32) for _ in range(3))
+    ref, rinfo = oracle.qflash_attention_dynamic(Qf, Kf, Vf, 64)
+    out, inf, _ = run_dynamic(gpu, Qf, Kf, Vf, 64)
+    assert inf.status == 0 and inf.params.astuple() == rinfo["params"].astuple()
+    assert np.array_equal(out, ref)
+
+
 # ------------------------------------------------------------------------------ ABI behaviour
 
 

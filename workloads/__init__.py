@@ -152,6 +152,18 @@ BASELINE_CONFIGS = CONFIG_ORDER[:5]           # the five benchmark configuration
 TABLE1_CONFIGS = CONFIG_ORDER[5:]             # Table 1 at batch 1 and 8
 
 
+def make_float_qkv(name: str, batch: Optional[int] = None):
+    """The float32 Q, K, V a non-windowed workload is quantised from (same seed, same draws):
+    input of the dynamic-quantisation path."""
+    shape, dist, sigma, ofrac, _, windowed = CONFIGS[name]
+    if windowed:
+        raise ValueError("float inputs are offered for the non-windowed workloads")
+    if batch is not None:
+        shape = (int(batch),) + tuple(shape[1:])
+    rng = np.random.default_rng(1000 + CONFIG_ORDER.index(name) + 1)
+    return tuple(_draw(rng, shape, dist, sigma, ofrac) for _ in range(3))
+
+
 def head_gains(H: int) -> np.ndarray:
     """Deterministic spread of per-head ranges, 1/4 .. 4 (geometric), used by the per-head variant."""
     return np.exp2(np.linspace(-2.0, 2.0, H)) if H > 1 else np.ones(1)
