@@ -28,6 +28,7 @@
 // weights come from a table in LDS instead.  Inline assembly never reads a register written by an
 // MFMA: the compiler only places the wait states of the matrix pipeline for reads it can see.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "qflash_internal.h"
@@ -441,11 +442,24 @@ __device__ __forceinline__ ExpConst make_exp_const(const QflashHeadConsts& h) {
 
 // Constants of the head that (batch, head) pair bh belongs to.  bh is uniform over the wavefront,
 // so these are scalar loads from the kernel arguments.
-// With dynamic quantisation they were computed on the GPU and live in device memory.
+// With dynamic quantisation they were computed on the GPU and live in device memory: read field
+// by field into scalar registers (selecting between the two structures by pointer would turn every
+// access, the table loads included, into generic-address loads).
 __device__ __forceinline__ QflashHeadConsts head_consts(const QflashKernelArgs& a, int bh) {
-    if (a.hc_dev) return *a.hc_dev;
-    return a.hc[a.per_head ? bh % a.H : 0];
+    QflashHeadConsts h = a.hc[a.per_head ? bh % a.H : 0];
+    if (a.hc_dev) {
+        const int* g = (const int*)a.hc_dev;     // x_shift, s_inv, exp_mul, p_mul, p_shift, a_mul, x_floor
+        h.x_shift = __builtin_amdgcn_readfirstlane(g[0]);
+        h.s_inv = __builtin_amdgcn_readfirstlane(g[1]);
+        h.exp_mul = __builtin_amdgcn_readfirstlane(g[2]);
+        h.p_mul = __builtin_amdgcn_readfirstlane(g[3]);
+        h.p_shift = __builtin_amdgcn_readfirstlane(g[4]);
+        h.a_mul = __builtin_amdgcn_readfirstlane(g[5]);
+        h.x_floor = __builtin_amdgcn_readfirstlane(g[6]);
+    }
+    return h;
 }
+static_assert(offsetof(QflashHeadConsts, x_floor) == 24, "field order read by head_consts");
 
 // 4x4 byte transpose: rows r[0..3] (byte f = feature f) -> o[f] = (r0.f, r1.f, r2.f, r3.f).
 // v_perm_b32 picks result bytes from the 8 bytes {first operand (4..7), second operand (0..3)}.
