@@ -29,6 +29,7 @@ constexpr int kTableMaxBytes = 40 * 1024;
 struct qflash_ctx {
     int device;
     int lds_limit;        // LDS bytes one workgroup may allocate on this device
+    int n_cu;             // compute units
     int use_table;        // QFLASH_CFG_EXP_TABLE
     uint8_t* tables;      // device, kTableSlots x kTableMaxBytes
     int n_slots;          // slots in use
@@ -77,6 +78,7 @@ extern "C" int qflash_create(qflash_ctx** out, int device_id) {
         lds = 64 * 1024;
     }
     c->lds_limit = lds;
+    c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     c->use_table = 1;
     c->n_slots = 0;
     c->tables = nullptr;
@@ -129,12 +131,13 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
                    const qflash_params* p, bool per_head, void* hip_stream,
                    const QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0) {
     if (!ctx) return QFLASH_ERR_NULL;
-    int device, lds_limit;
+    int device, lds_limit, n_cu;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
         device = ctx->device;
         lds_limit = ctx->lds_limit;
+        n_cu = ctx->n_cu;
     }
     if (!Q || !K || !V || !O || (!p && !hc_dev)) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
@@ -164,6 +167,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.out_round = hc_dev ? out_round_dev : p[0].out_round;
     a.per_head = per_head ? 1 : 0;
     a.hc_dev = hc_dev;
+    a.n_cu = n_cu;
     bool all_k0 = hc_dev == nullptr;
     for (int h = 0; h < n_p; ++h) {
         if (!qflash_fill_head_consts(p[h], &a.hc[h])) return QFLASH_ERR_PARAM;
@@ -172,6 +176,8 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.exp_mode = all_k0 ? 1 : 0;
     a.lut_bytes_max = 0;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
+    // wave priority by dispatch round: only for launches of two to four rounds (0 = off)
+    if (a.n_units <= n_cu || a.n_units > 4 * n_cu) a.n_cu = 0;
 
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }

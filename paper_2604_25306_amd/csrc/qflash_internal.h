@@ -35,6 +35,7 @@ struct QflashKernelArgs {
     int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
     int pipelined;           // resident only: K/V tiles are staged one ahead of their use
+    int n_cu;                // compute units of the device if wave priority alternates by dispatch round, else 0
     // weight mode of the launch (uniform over heads): 2 = every head reads its table,
     // 1 = arithmetic with x_shift == 0 for every head, 0 = arithmetic
     int exp_mode;
@@ -53,7 +54,7 @@ int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_
 // (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd).
 // Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
-int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);
+int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);   // n_cu is the caller's
 
 // 1 if the resident kernel can also hold a weight table of table_bytes in LDS and copying it pays.
 int qflash_table_fits(const QflashKernelArgs& args, int d, int table_bytes, int lds_limit);

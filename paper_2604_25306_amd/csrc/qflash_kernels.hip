@@ -532,6 +532,15 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int wg = blockIdx.x;
     const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
     if (unit >= a.n_units) return;
+    // Workgroups are handed out in index order, one per compute unit and round.  In a launch of
+    // only a few rounds, alternating the wave priority by round puts a newcomer ahead of the older
+    // workgroup it shares the unit with: the newcomer is the one the end of the launch waits for.
+    // (Only a hint: correctness does not depend on placement.  With many rounds it starves every
+    // other workgroup and costs time, so the host switches it off there.)
+    if (a.n_cu > 0) {
+        if ((wg / a.n_cu) & 1) __builtin_amdgcn_s_setprio(0);
+        else __builtin_amdgcn_s_setprio(3);
+    }
 
     const int wg_tid = threadIdx.x, wg_nthr = blockDim.x;
     const int lane = wg_tid & 63;
