@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--workload", default=None)
     ap.add_argument("--kv-tile", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the launches from a captured HIP graph of 50 steps (for workloads so "
+                         "small that the Python call per launch, about 10 us, is what the eager loop measures)")
     ap.add_argument("--dynamic", action="store_true",
                     help="start from float32 Q, K, V: abs-max, scales, constants and quantisation on "
                          "the GPU in front of the attention kernel (qflash_attention_dynamic); one "
@@ -99,13 +102,38 @@ def main():
         else:
             ctx.attention(q, k, v, o, params, tile, bias=bias)
 
+    GRAPH_STEPS = 50
+    graphs = {}
+
+    def graph_for(rotate):
+        # one graph of GRAPH_STEPS consecutive steps, captured after a warm-up on the capture stream
+        if rotate not in graphs:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for i in range(len(sets) + 2):
+                    step(i)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(GRAPH_STEPS):
+                    step(i if rotate else 0)
+            graphs[rotate] = g
+        return graphs[rotate]
+
     def timed(n_steps, rotate=True):
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g = graph_for(rotate) if args.graph else None
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record()
-        for i in range(n_steps):
-            step(i if rotate else 0)
+        if g is not None:
+            for _ in range(n_steps // GRAPH_STEPS):
+                g.replay()
+        else:
+            for i in range(n_steps):
+                step(i if rotate else 0)
         ev1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
@@ -119,6 +147,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.graph:
+        args.steps = max(GRAPH_STEPS, args.steps // GRAPH_STEPS * GRAPH_STEPS)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -154,7 +184,7 @@ def main():
         "config": {"workload": name, "B": B, "H": H, "N": N, "d": d, "kv_tile": tile,
                    "bias": wl.bias is not None,
                    "scales": "dynamic" if args.dynamic else "per_head" if args.per_head else "per_tensor",
-                   "input_sets_rotated": len(sets)},
+                   "input_sets_rotated": len(sets), "launch": "hip_graph" if args.graph else "eager"},
         "kernel_us_events": kern_s * 1e6,
         "hot_cache": {"kernel_us_events": ev_hot / args.steps * 1e6,
                       "tops": ops / (ev_hot / args.steps) / 1e12},

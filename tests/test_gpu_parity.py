@@ -391,6 +391,43 @@ def test_stream_determinism_and_full_overwrite(gpu):
     assert np.array_equal(a, ref) and np.array_equal(b, ref) and np.array_equal(c, ref)
 
 
+def test_graph_capture_and_replay(gpu):
+    """The call path allocates nothing and never waits for the GPU, so a launch can be captured in a
+    HIP graph: every replay (with eager work and synchronisations in between, and with the inputs
+    changed in place) must give the bytes of the eager call and of the oracle."""
+    torch, qf, ctx = gpu
+    dev = torch.device("cuda:0")
+    wl = make_workload("a2_deit_s_b8")
+    p = oracle.derive_params(wl.sQ, wl.sK, wl.shape[-1])
+    lp = lib_params(qf, p)
+    q, k, v = (torch.from_numpy(x).to(dev) for x in (wl.Q, wl.K, wl.V))
+    o = torch.zeros_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):                       # warm-up on the capture stream: table, kernel attributes
+            ctx.attention(q, k, v, o, lp, 64)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ctx.attention(q, k, v, o, lp, 64)
+    ref = oracle.qflash_attention(wl.Q, wl.K, wl.V, p, 64)
+    for rep in range(4):
+        o.fill_(0x11)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(o.cpu().numpy(), ref), "replay %d" % rep
+    # new inputs in the same buffers: the graph reads what is there at replay time
+    Q2 = np.ascontiguousarray(wl.Q[::-1])
+    q.copy_(torch.from_numpy(Q2).to(dev))
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert np.array_equal(o.cpu().numpy(), oracle.qflash_attention(Q2, wl.K, wl.V, p, 64))
+
+
 def test_table_cache_many_constants_and_streams(gpu):
     """More distinct constants than the context has table slots (later ones fall back to the
     arithmetic mode), and the same constants on two streams (each builds its own table)."""
