@@ -643,17 +643,20 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     st.l = 0;
     st.m = SB ? (int)((unsigned)kMInit + (unsigned)kAccBias) : kMInit;
 
-    // ---- stage the weight table (L2-resident, shared by every workgroup of the launch): four
-    //      16-byte pieces per thread in flight at a time
+    // ---- stage the weight table (L2-resident, shared by every workgroup of the launch): six
+    //      16-byte pieces per thread in flight at a time, which covers the largest table in one
+    //      round trip for a workgroup of seven wavefronts (a second round for a few left-over
+    //      pieces would cost every wavefront another L2 latency at the barrier)
     if (XM == kExpTable) {
+        constexpr int TB_ = 6;
         const int nch = hc.lut_bytes / 16;
-        for (int ch0 = wg_tid; ch0 < nch; ch0 += 4 * wg_nthr) {
-            v4i t[4];
+        for (int ch0 = wg_tid; ch0 < nch; ch0 += TB_ * wg_nthr) {
+            v4i t[TB_];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < TB_; ++u)
                 if (ch0 + u * wg_nthr < nch) t[u] = *(const v4i*)(hc.lut + 16 * (ch0 + u * wg_nthr));
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < TB_; ++u)
                 if (ch0 + u * wg_nthr < nch) *(v4i*)(smem + 16 * (ch0 + u * wg_nthr)) = t[u];
         }
     }
