@@ -375,6 +375,47 @@ def test_dynamic_headline_shape_full_size(gpu):
     assert np.array_equal(out, ref)
 
 
+# ------------------------------------------------------------------- seeded random sweep
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(gpu, seed):
+    """Shapes, tile size, scales, bias, exclusion, rounding mode and scale granularity drawn from a
+    seed: every kernel family and staging mode meets combinations no hand-written case lists."""
+    from workloads import quantize_per_head
+    rng = np.random.default_rng(70000 + seed)
+    d = int(rng.choice([32, 64]))
+    tile = int(rng.choice([64, 128]))
+    N = int(rng.choice([rng.integers(1, 65), rng.integers(65, 257), rng.integers(257, 700)]))
+    B, H = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+    shape = (B, H, N, d)
+    per_head = bool(rng.integers(0, 3) == 0)
+    out_round = int(rng.integers(0, 2))
+    q_gain = float(np.exp2(rng.uniform(-1.0, 3.0)))
+    Qf = (rng.standard_normal(shape) * q_gain).astype(np.float32)
+    Kf = rng.standard_normal(shape).astype(np.float32)
+    Vf = rng.standard_normal(shape).astype(np.float32)
+    if per_head:
+        gain = np.exp2(rng.uniform(-1.5, 2.5, size=H))[None, :, None, None].astype(np.float32)
+        Qf, Kf = Qf * gain, Kf * gain
+        (Q, sQ), (K, sK), (V, sV) = (quantize_per_head(x) for x in (Qf, Kf, Vf))
+        ps = [oracle.derive_params(sQ[h], sK[h], d, out_round=out_round) for h in range(H)]
+    else:
+        (Q, sQ), (K, sK), (V, sV) = (quantize_per_tensor(x) for x in (Qf, Kf, Vf))
+        ps = oracle.derive_params(sQ, sK, d, out_round=out_round)
+    bias = None
+    if rng.integers(0, 3) == 0:
+        bB, bH = int(rng.choice([1, B])), int(rng.choice([1, H]))
+        bias = rng.integers(-5000, 5000, size=(bB, bH, N, N)).astype(np.int32)
+        bias[rng.random(bias.shape) < 0.15] = EXCLUDED
+        if N > 3:
+            bias[0, 0, N // 2, :] = EXCLUDED           # a fully excluded row
+    print("config", shape, "tile", tile, "per_head", per_head, "round", out_round, "bias", None if bias is None else bias.shape, flush=True)
+    ref = oracle.qflash_attention(Q, K, V, ps, tile, bias=bias)
+    out = run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=bias) if per_head else run_gpu(gpu, Q, K, V, ps, tile, bias=bias)
+    assert np.array_equal(out, ref)
+
+
 # ------------------------------------------------------------------------------ ABI behaviour
 
 
