@@ -16,17 +16,22 @@
 //
 // Two kernels share the per-tile code:
 //   resident  one workgroup = one (batch, head) pair and up to 8 (N <= 256) or 12 wavefronts of
-//             32 query rows, or several short pairs (windowed attention) side by side; the whole
-//             K and V^T of each pair are staged in LDS once (N up to about 1100), after which
-//             the wavefronts run independently, with no barrier in the KV loop.
+//             32 query rows, or several short pairs (windowed attention) side by side; K and V^T
+//             of each pair live in LDS (N up to about 1100), every KV tile in a region of its
+//             own.  They are staged either all at once (one barrier, then no barrier in the KV
+//             loop) or tile by tile, one tile ahead of its use, with the next tile's global loads
+//             in flight during the arithmetic and one barrier per tile.
 //   stream    one workgroup = 128 query rows; KV tiles are staged per iteration (any N).
 //
-// The element-wise integer softmax is the binding resource (about ten VALU operations per score
-// against 256 MFMA operations and 1.3 HBM bytes), so the per-element path is written for the
-// full-rate 24-bit multiplier (v_mul_hi_i32_i24, v_mad_i32_i24), leaves its int8 result in the top
-// byte of a product and gathers four of them with v_perm_b32; where the constants allow it the
-// weights come from a table in LDS instead.  Inline assembly never reads a register written by an
-// MFMA: the compiler only places the wait states of the matrix pipeline for reads it can see.
+// The element-wise integer softmax is what takes the time (about six VALU instructions per score
+// a lane handles, against 256 MFMA operations and 1.3 HBM bytes per score), so the per-element
+// path is kept short: where the constants allow it the int8 weight of a score comes from a table
+// in LDS (one saturating subtraction and one byte read); otherwise Algorithm 2 runs on the
+// 24-bit multiplier (v_mul_hi_i32_i24), leaves its int8 result in the top byte of a product, and
+// four of them are gathered with v_perm_b32.  Accumulators (and, where registers allow, scores)
+// carry an offset of 2^31 that turns the rescale into a multiply-high and an add and the table
+// index into a single subtraction.  Inline assembly never reads a register written by an MFMA:
+// the compiler only places the wait states of the matrix pipeline for reads it can see.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
