@@ -134,6 +134,41 @@ int qflash_attention_per_head(qflash_ctx* ctx,
                               const qflash_params* p /* host, H entries */, void* hip_stream);
 
 /*
+ * Bias in the layout the kernels read fastest.  The additive integer bias of windowed attention
+ * (Section 5: Swin; relative-position bias plus the mask of shifted windows, step 1 of
+ * Algorithm 1 with the bias added to S) is fixed per layer, while the plain [N,N] layout makes
+ * every lane of a wavefront read its own row.  qflash_pack_bias rewrites it once so that the 64
+ * lanes of a wavefront read 1 KiB in a row; qflash_attention_packed_bias then computes exactly
+ * what qflash_attention / qflash_attention_per_head compute from the plain bias.
+ *
+ * Layout of `packed` (int32): [bias_B*bias_H][R][R][4][64][4] with R = ceil(N/32); the element
+ * [s][rb][cb][a][l][b] is bias[s][min(32*rb + l%32, N-1)][c] with c = 32*cb + 8*a + 4*(l/32) + b,
+ * or QFLASH_EXCLUDED where c >= N.  It depends on N only, not on kv_tile or d.
+ *
+ *   qflash_packed_bias_bytes  size of `packed` in bytes; 0 if the extents are not supported.
+ *   qflash_pack_bias          bias: device int32 [bias_B,bias_H,N,N], 4-byte aligned, read only;
+ *                             packed: device, 16-byte aligned, packed_bytes >= the size above,
+ *                             caller-owned.  Enqueues one kernel on hip_stream; allocates nothing.
+ *                             Errors: CTX, NULL, SHAPE (also: packed_bytes too small), ALIGN,
+ *                             DEVICE, LAUNCH.
+ *   qflash_attention_packed_bias  as qflash_attention with n_params == 1 (p[0] serves every head)
+ *                             or as qflash_attention_per_head with n_params == H; packed_bias must
+ *                             not be NULL and must have been written for the same bias_B, bias_H, N.
+ *                             Errors: as those; PARAM also for another n_params.
+ */
+size_t qflash_packed_bias_bytes(int bias_B, int bias_H, int N);
+
+int qflash_pack_bias(qflash_ctx* ctx, const int32_t* bias, int bias_B, int bias_H, int N,
+                     int32_t* packed /* device */, size_t packed_bytes, void* hip_stream);
+
+int qflash_attention_packed_bias(qflash_ctx* ctx,
+                                 const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
+                                 const int32_t* packed_bias, int bias_B, int bias_H,
+                                 int B, int H, int N, int d, int kv_tile,
+                                 const qflash_params* p /* host, n_params entries */, int n_params,
+                                 void* hip_stream);
+
+/*
  * Dynamic quantisation (Section 5, evaluation set-up: activation scales computed on the fly;
  * Eq. 1-2 with b = 8) in front of the same pass, entirely on the GPU and without waiting for it:
  * per-tensor abs-max of the float32 tensors Qf, Kf, Vf, scales s_X = max|X| / 127, quantisation

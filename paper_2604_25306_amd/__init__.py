@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     qflash_params_from_scales, qflash_create, qflash_configure, qflash_attention,
     qflash_attention_per_head, qflash_dynamic_workspace_bytes, qflash_attention_dynamic, DynamicInfo,
     qflash_destroy, qflash_strerror, EXCLUDED, ERR, CFG_EXP_TABLE,
-    MAX_PARAM_HEADS,
+    MAX_PARAM_HEADS, qflash_packed_bias_bytes, qflash_pack_bias, qflash_attention_packed_bias,
 )

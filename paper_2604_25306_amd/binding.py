@@ -16,6 +16,7 @@ ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, 
 
 EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
            "qflash_attention_per_head", "qflash_dynamic_workspace_bytes", "qflash_attention_dynamic",
+           "qflash_packed_bias_bytes", "qflash_pack_bias", "qflash_attention_packed_bias",
            "qflash_destroy", "qflash_strerror"]
 
 MAX_PARAM_HEADS = 64
@@ -75,6 +76,12 @@ def load_library():
                                                  ctypes.c_size_t, vp]
         lib.qflash_attention_per_head.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
         lib.qflash_attention.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
+        lib.qflash_packed_bias_bytes.restype = ctypes.c_size_t
+        lib.qflash_packed_bias_bytes.argtypes = [ci, ci, ci]
+        lib.qflash_pack_bias.restype = ci
+        lib.qflash_pack_bias.argtypes = [vp, vp, ci, ci, ci, vp, ctypes.c_size_t, vp]
+        lib.qflash_attention_packed_bias.restype = ci
+        lib.qflash_attention_packed_bias.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, ci, vp]
         lib.qflash_configure.restype = ci
         lib.qflash_configure.argtypes = [vp, ci, ci]
         lib.qflash_destroy.restype = ci
@@ -168,6 +175,51 @@ def qflash_attention_per_head(ctx: int, Q, K, V, O, params, kv_tile: int, bias=N
         raise QFlashError(rc, "qflash_attention_per_head")
 
 
+def qflash_packed_bias_bytes(bias_B: int, bias_H: int, N: int) -> int:
+    return int(load_library().qflash_packed_bias_bytes(int(bias_B), int(bias_H), int(N)))
+
+
+def qflash_pack_bias(ctx: int, bias, packed, stream: Optional[int] = None) -> None:
+    """Rewrite ``bias`` (contiguous int32 CUDA tensor [bias_B,bias_H,N,N]) into ``packed`` (contiguous
+    int32 CUDA tensor of at least ``qflash_packed_bias_bytes`` bytes) for ``qflash_attention_packed_bias``."""
+    import torch
+    if bias.dtype != torch.int32 or not bias.is_cuda or not bias.is_contiguous() or bias.dim() != 4 \
+            or bias.shape[2] != bias.shape[3]:
+        raise ValueError("bias must be a contiguous int32 CUDA tensor [bias_B,bias_H,N,N]")
+    if packed.dtype != torch.int32 or not packed.is_cuda or not packed.is_contiguous():
+        raise ValueError("packed must be a contiguous int32 CUDA tensor")
+    if stream is None:
+        stream = torch.cuda.current_stream(bias.device).cuda_stream
+    rc = load_library().qflash_pack_bias(
+        ctypes.c_void_p(ctx), _ptr(bias), int(bias.shape[0]), int(bias.shape[1]), int(bias.shape[2]),
+        _ptr(packed), int(packed.numel()) * 4, ctypes.c_void_p(stream))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_pack_bias")
+
+
+def qflash_attention_packed_bias(ctx: int, Q, K, V, O, params, kv_tile: int, packed, bias_B: int,
+                                 bias_H: int, stream: Optional[int] = None) -> None:
+    """The forward pass with a bias packed by ``qflash_pack_bias`` for the same bias_B, bias_H, N.
+    ``params``: one QFlashParams or a sequence of H."""
+    import torch
+    args, st = _marshal(Q, K, V, O, None, stream)
+    if packed.dtype != torch.int32 or not packed.is_cuda or not packed.is_contiguous():
+        raise ValueError("packed must be a contiguous int32 CUDA tensor")
+    # same figure as qflash_packed_bias_bytes, without a call into the library per launch
+    if packed.numel() < int(bias_B) * int(bias_H) * ((args[9] + 31) // 32) ** 2 * 1024:
+        raise ValueError("packed is smaller than qflash_packed_bias_bytes(bias_B, bias_H, N)")
+    if isinstance(params, QFlashParams):
+        pp, n_p = ctypes.byref(params), 1
+    else:
+        params = list(params)
+        pp, n_p = ctypes.cast((QFlashParams * len(params))(*params), ctypes.POINTER(QFlashParams)), len(params)
+    rc = load_library().qflash_attention_packed_bias(
+        ctypes.c_void_p(ctx), args[0], args[1], args[2], args[3], _ptr(packed), int(bias_B), int(bias_H),
+        args[7], args[8], args[9], args[10], int(kv_tile), pp, n_p, st)
+    if rc != 0:
+        raise QFlashError(rc, "qflash_attention_packed_bias")
+
+
 def qflash_dynamic_workspace_bytes(B: int, H: int, N: int, d: int) -> int:
     return int(load_library().qflash_dynamic_workspace_bytes(int(B), int(H), int(N), int(d)))
 
@@ -215,6 +267,19 @@ class Context:
             qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
         else:
             qflash_attention_per_head(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
+
+    def pack_bias(self, bias, stream=None):
+        """Returns the packed copy of ``bias`` (a new int32 CUDA tensor) for ``attention_packed_bias``."""
+        import torch
+        n = qflash_packed_bias_bytes(bias.shape[0], bias.shape[1], bias.shape[2])
+        if n == 0:
+            raise ValueError("bias extents are not supported")
+        packed = torch.empty(n // 4, dtype=torch.int32, device=bias.device)
+        qflash_pack_bias(self.handle, bias, packed, stream)
+        return packed
+
+    def attention_packed_bias(self, Q, K, V, O, params, kv_tile, packed, bias_B, bias_H, stream=None):
+        qflash_attention_packed_bias(self.handle, Q, K, V, O, params, kv_tile, packed, bias_B, bias_H, stream)
 
     def attention_dynamic(self, Qf, Kf, Vf, O, kv_tile, workspace, info=None, out_round=0, stream=None):
         qflash_attention_dynamic(self.handle, Qf, Kf, Vf, O, kv_tile, workspace, info, out_round, stream)

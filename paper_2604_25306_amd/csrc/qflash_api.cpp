@@ -129,7 +129,7 @@ namespace {
 int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
                    const int32_t* bias, int bias_B, int bias_H, int B, int H, int N, int d, int kv_tile,
                    const qflash_params* p, bool per_head, void* hip_stream,
-                   const QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0) {
+                   const QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0, bool bias_packed = false) {
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit, n_cu;
     {
@@ -147,6 +147,9 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     if (bias) {
         if (bias_B < 1 || bias_H < 1) return QFLASH_ERR_SHAPE;
         if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+        if (bias_packed && qflash_packed_bias_words(bias_B * bias_H, N) >= ((int64_t)1 << 29)) return QFLASH_ERR_SHAPE;
+    } else if (bias_packed) {
+        return QFLASH_ERR_NULL;
     }
     if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
     const int n_p = hc_dev ? 0 : per_head ? H : 1;
@@ -155,7 +158,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         if (p[h].out_round != p[0].out_round) return QFLASH_ERR_PARAM;   // one rounding mode per call
     }
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
-    if (bias && ((uintptr_t)bias & 3u)) return QFLASH_ERR_ALIGN;
+    if (bias && ((uintptr_t)bias & (bias_packed ? 15u : 3u))) return QFLASH_ERR_ALIGN;
 
     static_assert(QFLASH_MAX_PARAM_HEADS == kQflashMaxParamHeads, "header and kernel arguments disagree");
     QflashKernelArgs a;
@@ -163,6 +166,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.bias = bias;
     a.bias_B = bias ? bias_B : 1;
     a.bias_H = bias ? bias_H : 1;
+    a.bias_packed = bias_packed ? 1 : 0;
     a.B = B; a.H = H; a.N = N;
     a.out_round = hc_dev ? out_round_dev : p[0].out_round;
     a.per_head = per_head ? 1 : 0;
@@ -252,6 +256,50 @@ extern "C" int qflash_attention_per_head(qflash_ctx* ctx, const int8_t* Q, const
                                          int H, int N, int d, int kv_tile, const qflash_params* p,
                                          void* hip_stream) {
     return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, true, hip_stream);
+}
+
+extern "C" size_t qflash_packed_bias_bytes(int bias_B, int bias_H, int N) {
+    if (bias_B < 1 || bias_H < 1 || N < 1 || N > QFLASH_MAX_N) return 0;
+    if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return 0;
+    const long long words = qflash_packed_bias_words(bias_B * bias_H, N);
+    if (words >= ((int64_t)1 << 29)) return 0;
+    return (size_t)words * 16;
+}
+
+extern "C" int qflash_pack_bias(qflash_ctx* ctx, const int32_t* bias, int bias_B, int bias_H, int N,
+                                int32_t* packed, size_t packed_bytes, void* hip_stream) {
+    if (!ctx) return QFLASH_ERR_NULL;
+    int device;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+        device = ctx->device;
+    }
+    if (!bias || !packed) return QFLASH_ERR_NULL;
+    const size_t need = qflash_packed_bias_bytes(bias_B, bias_H, N);
+    if (need == 0) return QFLASH_ERR_SHAPE;
+    if (packed_bytes < need) return QFLASH_ERR_SHAPE;
+    if (((uintptr_t)bias & 3u) || ((uintptr_t)packed & 15u)) return QFLASH_ERR_ALIGN;
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }
+    if (cur != device && hipSetDevice(device) != hipSuccess) {
+        (void)hipGetLastError();
+        return QFLASH_ERR_DEVICE;
+    }
+    const int rc = qflash_launch_pack_bias(bias, bias_B * bias_H, N, packed, hip_stream);
+    if (cur != device) (void)hipSetDevice(cur);
+    if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
+    return QFLASH_OK;
+}
+
+extern "C" int qflash_attention_packed_bias(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
+                                            int8_t* O, const int32_t* packed_bias, int bias_B, int bias_H,
+                                            int B, int H, int N, int d, int kv_tile, const qflash_params* p,
+                                            int n_params, void* hip_stream) {
+    if (n_params != 1 && n_params != H) return QFLASH_ERR_PARAM;
+    if (!packed_bias) return QFLASH_ERR_NULL;
+    return attention_impl(ctx, Q, K, V, O, packed_bias, bias_B, bias_H, B, H, N, d, kv_tile, p,
+                          n_params == H && H > 1, hip_stream, nullptr, 0, true);
 }
 
 // Workspace layout of the dynamic entry point: [int8 Q | int8 K | int8 V | constants | abs-max scratch]

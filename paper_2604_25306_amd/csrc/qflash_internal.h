@@ -26,11 +26,13 @@ struct QflashKernelArgs {
     int8_t* O;
     const int32_t* bias;   // nullptr: no bias
     int bias_B, bias_H;
+    int bias_packed;       // bias is in the lane-major layout written by qflash_launch_pack_bias
     int B, H, N;
     int out_round;
     // work decomposition: one unit = (batch*head, query tile); XCD x owns units
     // [x*units_per_xcd, (x+1)*units_per_xcd)
     int rows_per_wg, n_qtiles, n_units, units_per_xcd;
+    int xcd_period;          // 0, or the number of units after which the bias slices repeat (a multiple of 8)
     int waves_per_head;      // wavefronts that serve one (batch, head) pair inside a workgroup
     int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
@@ -51,7 +53,7 @@ struct QflashKernelArgs {
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 
 // Choose the kernel variant for BH heads of N rows and fill the work decomposition fields
-// (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd).
+// (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd, xcd_period; reads bias, bias_B, H).
 // Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
 int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);   // n_cu is the caller's
@@ -61,6 +63,11 @@ int qflash_table_fits(const QflashKernelArgs& args, int d, int table_bytes, int 
 
 // Enqueue the kernel that fills a weight table of n entries (n_padded bytes) for the constants hc.
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashHeadConsts& hc, void* stream);
+
+// Bias in the lane-major layout the kernels read with 16-byte loads: number of 16-byte words for
+// `slices` = bias_B * bias_H matrices of N x N, and the kernel that writes them from the plain layout.
+long long qflash_packed_bias_words(int slices, int N);
+int qflash_launch_pack_bias(const int32_t* bias, int slices, int N, int32_t* packed, void* stream);
 
 // Enqueue the front end of the dynamic pipeline: abs-max of the three float32 tensors of n elements
 // each (n a multiple of 4), derivation of the scales and constants into *hc_dev (and *info if not

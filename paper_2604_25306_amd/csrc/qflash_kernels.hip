@@ -23,6 +23,11 @@
 //             in flight during the arithmetic and one barrier per tile.
 //   stream    one workgroup = 128 query rows; KV tiles are staged per iteration (any N).
 //
+// An additive int32 bias (windowed attention) comes in one of two layouts, each a template variant:
+// plain [N,N], where every lane reads its own row dword by dword, or packed lane-major (see
+// bias_lane_base), where a wavefront reads 1 KiB per instruction and keys beyond the sequence are
+// already excluded.
+//
 // The element-wise integer softmax is what takes the time (about six VALU instructions per score
 // a lane handles, against 256 MFMA operations and 1.3 HBM bytes per score), so the per-element
 // path is kept short: where the constants allow it the int8 weight of a score comes from a table
@@ -194,19 +199,22 @@ struct RowState {
 // is a single unsigned saturating subtraction per score; the maximum is taken unsigned and
 // RowState::m holds m + 2^31.  Algorithm 2 for alpha only sees differences, which are unchanged.
 enum { kExpShift = 0, kExpShift0 = 1, kExpTable = 2 };
+// Bias of a kernel variant: none, the plain [N,N] layout, or the lane-major packed layout.
+enum { kBiasNone = 0, kBiasPlain = 1, kBiasPacked = 2 };
 
 // Biased scores need 16 more registers; they are used where the kernel variant has them to spare.
-template <int D, int BC, bool BIAS, bool NARROW, int XM>
+template <int D, int BC, int BIAS, bool NARROW, int XM>
 constexpr bool score_biased() { return XM == kExpTable && !BIAS && D == 64 && (BC == 64 || !NARROW); }
 
 template <bool SB>
 __device__ __forceinline__ int smax(int a, int b) { return SB ? (int)max((unsigned)a, (unsigned)b) : max(a, b); }
 
-template <int D, int BC, bool BIAS, int XM, bool SB, bool FULL, bool FIRST>
+template <int D, int BC, int BIAS, int XM, bool SB, bool FULL, bool FIRST>
 __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
                                             const int8_t* sV, int VROW, int n_valid_rt, int x_p,
-                                            const int32_t* bias_row /* + c0 */, const ExpConst& c,
-                                            int a_mul, int li, int g, const v16i& zb) {
+                                            const int32_t* bias_row /* + c0 */,
+                                            const v4i* bpre /* packed bias of this tile already in registers, or null */,
+                                            const ExpConst& c, int a_mul, int li, int g, const v16i& zb) {
     constexpr int KSTEPS = D / 32, TB = D / 32, KB = BC / 32;
     constexpr bool KZ = XM == kExpShift0;
     static_assert(!SB || (XM == kExpTable && !BIAS), "biased scores: table mode without bias only");
@@ -236,7 +244,17 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4) {
             const int cb = 32 * kb + 8 * a4;            // first kv row of the group for g = 0
-            if (cb < n_valid && (BIAS || cb + 8 > n_valid)) {
+            if (BIAS == kBiasPacked) {
+                // Packed bias: the four values of this lane's group are one 16-byte word, the 64
+                // lanes of the wavefront read 1 KiB in a row; columns beyond the sequence hold the
+                // exclusion mark already.
+                if (cb < n_valid) {
+                    const v4i bv = bpre ? bpre[4 * kb + a4] : *(const v4i*)(bias_row + (4 * kb + a4) * 256);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        s[kb][4 * a4 + b] = __builtin_elementwise_add_sat(s[kb][4 * a4 + b], bv[b]);
+                }
+            } else if (cb < n_valid && (BIAS || cb + 8 > n_valid)) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const int col = cb + 4 * g + b;
@@ -520,7 +538,36 @@ extern __shared__ __align__(16) int8_t smem[];
 template <bool NARROW>
 constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
 
-template <int D, int BC, bool BIAS, bool NARROW, int XM>
+// Which unit of work a workgroup takes.  Consecutive workgroup indices go to consecutive XCDs
+// (each with its own L2), so XCD x = wg % 8 takes the units [x*units_per_xcd, (x+1)*units_per_xcd):
+// neighbouring heads share an L2.  With a bias whose slices repeat every xcd_period units (windowed
+// attention: the same windows in every image) XCD x instead takes the x-th eighth of every period,
+// so that each L2 only ever sees an eighth of the bias.
+__device__ __forceinline__ int unit_of_workgroup(const QflashKernelArgs& a, int wg) {
+    const int x = wg & 7, k = wg >> 3;
+    if (a.xcd_period == 0) return x * a.units_per_xcd + k;
+    const int q = a.xcd_period >> 3;
+    return (k / q) * a.xcd_period + x * q + k % q;
+}
+
+// Where this lane's bias values start.  Plain layout [bias_B,bias_H,N,N]: the lane's row (lanes
+// beyond the sequence read row 0; their results are never stored).  Packed layout
+// [bias_B*bias_H][ceil(N/32) row blocks][ceil(N/32) column blocks][4 groups][64 lanes][4]: the
+// 16-byte word of lane (li, g) in group a4 of column block cb holds
+// bias[32*rb + li][32*cb + 8*a4 + 4*g + 0..3], which is exactly what the lane adds to its four
+// scores of that group, so one instruction of the wavefront reads 1 KiB in a row.
+__device__ __forceinline__ const int32_t* bias_lane_base(const QflashKernelArgs& a, int bh, int row0, int i,
+                                                        int li, int g) {
+    const int b = bh / a.H, h = bh % a.H, N = a.N;
+    const size_t slice = (size_t)(b % a.bias_B) * a.bias_H + (size_t)(h % a.bias_H);
+    if (a.bias_packed) {
+        const int nb = (N + 31) / 32;
+        return a.bias + ((slice * nb + (size_t)min(row0 / 32, nb - 1)) * nb) * 1024 + 4 * (32 * g + li);
+    }
+    return a.bias + slice * N * N + (size_t)(i < N ? i : 0) * N;
+}
+
+template <int D, int BC, int BIAS, bool NARROW, int XM>
 __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
@@ -535,7 +582,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int tbytes = XM == kExpTable ? a.lut_bytes_max : 0;   // LDS reserved for the table
 
     const int wg = blockIdx.x;
-    const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
+    const int unit = unit_of_workgroup(a, wg);
     if (unit >= a.n_units) return;
     // Workgroups are handed out in index order, one per compute unit and round.  In a launch of
     // only a few rounds, alternating the wave priority by round puts a newcomer ahead of the older
@@ -634,6 +681,20 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     v4i qreg[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) qreg[s] = *(const v4i*)(Qh + (size_t)min(i, N - 1) * D + 32 * s + 16 * g);
+    // ---- packed bias of the first tile (short head size only, where the registers are there):
+    //      fetched here, beside K, V and Q, its way through the cache hierarchy is over when the
+    //      barrier opens, instead of starting then.  Column blocks wholly beyond the sequence do not
+    //      exist in the packed layout and are skipped (the tile code skips them too).
+    const int32_t* bias_row = nullptr;
+    constexpr bool bias_packed = BIAS == kBiasPacked;
+    if (BIAS) bias_row = bias_lane_base(a, pair_valid ? bh : 0, row0, i, li, g);
+    constexpr bool BPRE_OK = bias_packed && D == 32 && BC == 64;
+    v4i bpre[BPRE_OK ? 4 * (BC / 32) : 1];
+    if (BPRE_OK) {
+#pragma unroll
+        for (int q = 0; q < 4 * (BC / 32); ++q)
+            if (32 * (q / 4) < N) bpre[q] = *(const v4i*)(bias_row + q * 256);
+    }
     // ---- loop-invariant registers, set up before any K/V tile is in flight
     const ExpConst c = make_exp_const(hc);
     constexpr bool SB = score_biased<D, BC, BIAS, NARROW, XM>();
@@ -683,6 +744,11 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // pending; loads complete in order, so that wait would cover the K/V tile in flight as well.
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) asm volatile("" : "+v"(qreg[s]));
+    if (BPRE_OK) {
+#pragma unroll
+        for (int q = 0; q < 4 * (BC / 32); ++q)
+            if (32 * (q / 4) < N) asm volatile("" : "+v"(bpre[q]));
+    }
     if (pipelined) write_tile(0, pf0);
     __syncthreads();
     // A wavefront without query rows leaves after the only barrier, unless it still has tiles to
@@ -690,20 +756,20 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const bool active = row0 < N && pair_valid;
     if (!active && !pipelined) return;
 
-    const int32_t* bias_row = nullptr;
-    if (BIAS) {
-        const int b = bh / a.H, h = bh % a.H;
-        bias_row = a.bias + ((size_t)(b % a.bias_B) * a.bias_H + (size_t)(h % a.bias_H)) * N * N +
-                   (size_t)(i < N ? i : 0) * N;
-    }
     // First tile (no rescale), the remaining full tiles as one straight-line loop body, then the
     // ragged tile if the sequence does not end on a tile boundary.
     const int n_full = N / BC, rem = N - n_full * BC;
+    // With a packed bias the keys beyond the sequence carry the exclusion mark (and K, V are zero
+    // there), so a last tile whose every 32-key block exists in the packed layout runs the
+    // straight-line code of a full tile instead of testing each group of keys.
+    const bool ragged_as_full = bias_packed && rem > BC - 32;
 #define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
     if (active)                                                                                              \
     process_tile<D, BC, BIAS, XM, SB, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,          \
                                                      sV + (J_) * BC, VROW, NV_, hc.lut_xp,                   \
-                                                     BIAS ? bias_row + (J_) * BC : nullptr, c, hc.a_mul, li, g, zb)
+                                                     BIAS ? bias_row + (J_) * (bias_packed ? BC * 32 : BC) : nullptr, \
+                                                     (BPRE_OK && (FIRST_)) ? bpre : nullptr,                 \
+                                                     c, hc.a_mul, li, g, zb)
     // Pipelined mode, around tile j: tile j+1 (loaded while tile j-1 was processed) goes to LDS and
     // the loads of tile j+2 are issued before the arithmetic of tile j; the barrier after it
     // publishes tile j+1, which every wavefront wrote long before.
@@ -723,9 +789,13 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
             QF_TILE(true, false, j, BC);
             QF_POST(j)
         }
-        if (rem > 0) QF_TILE(false, false, n_full, rem);
+        if (rem > 0) {
+            if (ragged_as_full) { QF_TILE(true, false, n_full, BC); }
+            else { QF_TILE(false, false, n_full, rem); }
+        }
     } else {
-        QF_TILE(false, true, 0, rem);
+        if (ragged_as_full) { QF_TILE(true, true, 0, BC); }
+        else { QF_TILE(false, true, 0, rem); }
     }
 #undef QF_TILE
 #undef QF_PRE
@@ -743,7 +813,7 @@ constexpr int kStreamWaves = 4;
 constexpr int kStreamThreads = kStreamWaves * 64;
 constexpr int kStreamRows = kStreamWaves * 32;
 
-template <int D, int BC, bool BIAS>
+template <int D, int BC, int BIAS>
 __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const QflashKernelArgs a) {
     constexpr bool NARROW = false;   // long sequences only
     constexpr int KSTEPS = D / 32;
@@ -753,7 +823,7 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
     __shared__ __align__(16) int8_t sV[D * VROW];
 
     const int wg = blockIdx.x;
-    const int unit = (wg & 7) * a.units_per_xcd + (wg >> 3);
+    const int unit = unit_of_workgroup(a, wg);
     if (unit >= a.n_units) return;
     const int qt = unit % a.n_qtiles;
     const int bh = unit / a.n_qtiles;
@@ -771,11 +841,8 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
     const int8_t* Kh = a.K + head_off;
     const int8_t* Vh = a.V + head_off;
     const int32_t* bias_row = nullptr;
-    if (BIAS) {
-        const int b = bh / a.H, h = bh % a.H;
-        bias_row = a.bias + ((size_t)(b % a.bias_B) * a.bias_H + (size_t)(h % a.bias_H)) * N * N +
-                   (size_t)(i < N ? i : 0) * N;
-    }
+    constexpr bool bias_packed = BIAS == kBiasPacked;
+    if (BIAS) bias_row = bias_lane_base(a, bh, row0, i, li, g);
     v4i qreg[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
@@ -808,13 +875,13 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
         __syncthreads();
         if (!wave_active) continue;   // uniform per wavefront; still takes part in the barriers
         const int n_valid = min(BC, N - c0);
-        const int32_t* brow = BIAS ? bias_row + c0 : nullptr;
+        const int32_t* brow = BIAS ? bias_row + (bias_packed ? c0 * 32 : c0) : nullptr;
         if (j == 0)
-            process_tile<D, BC, BIAS, kExpShift, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, hc.a_mul, li, g, zb);
+            process_tile<D, BC, BIAS, kExpShift, false, false, true>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, nullptr, c, hc.a_mul, li, g, zb);
         else if (n_valid == BC)
-            process_tile<D, BC, BIAS, kExpShift, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, 0, brow, c, hc.a_mul, li, g, zb);
+            process_tile<D, BC, BIAS, kExpShift, false, true, false>(st, qreg, sK, KROW, sV, VROW, BC, 0, brow, nullptr, c, hc.a_mul, li, g, zb);
         else
-            process_tile<D, BC, BIAS, kExpShift, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, c, hc.a_mul, li, g, zb);
+            process_tile<D, BC, BIAS, kExpShift, false, false, false>(st, qreg, sK, KROW, sV, VROW, n_valid, 0, brow, nullptr, c, hc.a_mul, li, g, zb);
     }
     if (!wave_active || i >= N) return;
     int8_t* Orow = a.O + head_off + (size_t)i * D;
@@ -842,7 +909,7 @@ __global__ __launch_bounds__(256) void qflash_build_table(uint8_t* tbl, int n, i
     tbl[i] = (uint8_t)p;
 }
 
-template <int D, int BC, bool BIAS, bool NARROW, int XM>
+template <int D, int BC, int BIAS, bool NARROW, int XM>
 int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, int threads, hipStream_t stream) {
     const dim3 grid((unsigned)(8 * a.units_per_xcd));
     auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW, XM>;
@@ -856,14 +923,14 @@ int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, 
     return (int)hipGetLastError();
 }
 
-template <int D, int BC, bool BIAS, bool NARROW>
+template <int D, int BC, int BIAS, bool NARROW>
 int launch_mode(const QflashKernelArgs& a, size_t lds, int lds_limit, int threads, hipStream_t st) {
     if (a.exp_mode == kExpTable) return launch_resident<D, BC, BIAS, NARROW, kExpTable>(a, lds, lds_limit, threads, st);
     if (a.exp_mode == kExpShift0) return launch_resident<D, BC, BIAS, NARROW, kExpShift0>(a, lds, lds_limit, threads, st);
     return launch_resident<D, BC, BIAS, NARROW, kExpShift>(a, lds, lds_limit, threads, st);
 }
 
-template <int D, int BC, bool BIAS>
+template <int D, int BC, int BIAS>
 int launch_dbc_bias(const QflashKernelArgs& a, bool resident, size_t lds, int lds_limit, int threads, hipStream_t st) {
     if (!resident) {
         const dim3 grid((unsigned)(8 * a.units_per_xcd));
@@ -876,8 +943,9 @@ int launch_dbc_bias(const QflashKernelArgs& a, bool resident, size_t lds, int ld
 
 template <int D, int BC>
 int launch_dbc(const QflashKernelArgs& a, bool resident, size_t lds, int lds_limit, int threads, hipStream_t st) {
-    return a.bias ? launch_dbc_bias<D, BC, true>(a, resident, lds, lds_limit, threads, st)
-                  : launch_dbc_bias<D, BC, false>(a, resident, lds, lds_limit, threads, st);
+    if (!a.bias) return launch_dbc_bias<D, BC, kBiasNone>(a, resident, lds, lds_limit, threads, st);
+    return a.bias_packed ? launch_dbc_bias<D, BC, kBiasPacked>(a, resident, lds, lds_limit, threads, st)
+                         : launch_dbc_bias<D, BC, kBiasPlain>(a, resident, lds, lds_limit, threads, st);
 }
 
 }  // namespace
@@ -923,6 +991,17 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     if (units >= (1ll << 30)) return -1;
     a->n_units = (int)units;
     a->units_per_xcd = (a->n_units + 7) / 8;
+    // Bias slices repeat every bias_B * H pairs: see unit_of_workgroup.
+    a->xcd_period = 0;
+    if (a->bias) {
+        const long long pairs = (long long)a->bias_B * a->H;
+        const long long period = a->heads_per_wg > 1 ? (pairs % a->heads_per_wg == 0 ? pairs / a->heads_per_wg : 0)
+                                                     : pairs * a->n_qtiles;
+        if (period >= 8 && period % 8 == 0 && period <= units) {
+            a->xcd_period = (int)period;
+            a->units_per_xcd = (int)(((units + period - 1) / period) * (period / 8));
+        }
+    }
     return 0;
 }
 
@@ -939,6 +1018,39 @@ int qflash_table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashHeadConsts& a, void* stream) {
     hipLaunchKernelGGL(qflash_build_table, dim3((unsigned)((n_padded + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, tbl, n, n_padded, x_p, a);
+    return (int)hipGetLastError();
+}
+
+// Plain bias [slices,N,N] -> the lane-major layout bias_lane_base() describes.  One thread per
+// 16-byte word.  Rows beyond the sequence repeat row N-1 (never stored), columns beyond it are
+// excluded.
+__global__ __launch_bounds__(256) void qflash_pack_bias_kernel(const int32_t* __restrict__ bias, int32_t* __restrict__ packed,
+                                                               int N, long long n_words) {
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_words) return;
+    const int nb = (N + 31) / 32;
+    const int lane = (int)(t & 63), a4 = (int)((t >> 6) & 3);
+    const long long blk = t >> 8;
+    const int cb = (int)(blk % nb), rb = (int)((blk / nb) % nb);
+    const long long slice = blk / ((long long)nb * nb);
+    const int li = lane & 31, g = lane >> 5;
+    const int row = min(32 * rb + li, N - 1), col0 = 32 * cb + 8 * a4 + 4 * g;
+    const int32_t* src = bias + (slice * N + row) * (long long)N;
+    v4i w;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) w[b] = col0 + b < N ? src[col0 + b] : INT32_MIN;
+    *(v4i*)(packed + 4 * t) = w;
+}
+
+long long qflash_packed_bias_words(int slices, int N) {
+    const long long nb = (N + 31) / 32;
+    return (long long)slices * nb * nb * 256;
+}
+
+int qflash_launch_pack_bias(const int32_t* bias, int slices, int N, int32_t* packed, void* stream) {
+    const long long n_words = qflash_packed_bias_words(slices, N);
+    hipLaunchKernelGGL(qflash_pack_bias_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, bias, packed, N, n_words);
     return (int)hipGetLastError();
 }
 

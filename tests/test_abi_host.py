@@ -86,6 +86,17 @@ def test_context_errors_without_gpu(lib):
                                          ctypes.byref(p), None) == qf.ERR["NULL"]
     assert lib.qflash_attention_per_head(bogus, one, one, one, one, None, 0, 0, 1, 1, 1, 64, 64,
                                          ctypes.byref(p), None) == qf.ERR["CTX"]
+    assert lib.qflash_attention_packed_bias(None, one, one, one, one, one, 1, 1, 1, 1, 1, 64, 64,
+                                            ctypes.byref(p), 1, None) == qf.ERR["NULL"]
+    assert lib.qflash_attention_packed_bias(bogus, one, one, one, one, one, 1, 1, 1, 1, 1, 64, 64,
+                                            ctypes.byref(p), 1, None) == qf.ERR["CTX"]
+    assert lib.qflash_pack_bias(None, one, 1, 1, 1, one, 4096, None) == qf.ERR["NULL"]
+    assert lib.qflash_pack_bias(bogus, one, 1, 1, 1, one, 4096, None) == qf.ERR["CTX"]
+    # size of the packed bias: ceil(N/32)^2 blocks of 4 KiB per matrix; 0 for unsupported extents
+    assert lib.qflash_packed_bias_bytes(64, 3, 49) == 64 * 3 * 4 * 4096
+    assert lib.qflash_packed_bias_bytes(1, 1, 197) == 49 * 4096
+    assert lib.qflash_packed_bias_bytes(1, 1, 0) == 0
+    assert lib.qflash_packed_bias_bytes(1 << 20, 1 << 10, 64) == 0
     h = ctypes.c_void_p()
     rc = lib.qflash_create(ctypes.byref(h), 9999)
     assert rc == qf.ERR["DEVICE"] and not h.value

@@ -33,24 +33,36 @@ def lib_params(qf, p: OracleParams):
     return qf.QFlashParams(*p.astuple())
 
 
-def run_gpu(gpu, Q, K, V, p, tile, bias=None, stream=None):
+def run_gpu(gpu, Q, K, V, p, tile, bias=None, stream=None, packed=False):
+    """p: one OracleParams or a list of H.  packed: hand the bias over in the lane-major layout."""
     torch, qf, ctx = gpu
     dev = torch.device("cuda:0")
     tQ, tK, tV = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (Q, K, V))
     tO = torch.full(Q.shape, 0x55, dtype=torch.int8, device=dev)
     tB = torch.from_numpy(np.ascontiguousarray(bias)).to(dev) if bias is not None else None
-    ctx.attention(tQ, tK, tV, tO, lib_params(qf, p), tile, bias=tB, stream=stream)
+    lp = lib_params(qf, p) if isinstance(p, OracleParams) else [lib_params(qf, x) for x in p]
+    if packed:
+        tP = ctx.pack_bias(tB, stream=stream)
+        ctx.attention_packed_bias(tQ, tK, tV, tO, lp, tile, tP, bias.shape[0], bias.shape[1], stream=stream)
+    else:
+        ctx.attention(tQ, tK, tV, tO, lp, tile, bias=tB, stream=stream)
     torch.cuda.synchronize()
     return tO.cpu().numpy()
 
 
-def check(gpu, Q, K, V, p, tile, bias=None, label=""):
-    print("case", label, Q.shape, "tile", tile, "bias", bias is not None, flush=True)
-    ref = oracle.qflash_attention(Q, K, V, p, tile, bias=bias)
-    out = run_gpu(gpu, Q, K, V, p, tile, bias=bias)
+def assert_same(out, ref, label):
     bad = np.argwhere(out != ref)
     assert bad.size == 0, "%s: %d mismatches, first at %s: gpu %d oracle %d" % (
         label, len(bad), bad[0], out[tuple(bad[0])], ref[tuple(bad[0])])
+
+
+def check(gpu, Q, K, V, p, tile, bias=None, label=""):
+    """Every case with a bias runs twice on the GPU: plain bias, and the same bias packed."""
+    print("case", label, Q.shape, "tile", tile, "bias", bias is not None, flush=True)
+    ref = oracle.qflash_attention(Q, K, V, p, tile, bias=bias)
+    assert_same(run_gpu(gpu, Q, K, V, p, tile, bias=bias), ref, label)
+    if bias is not None:
+        assert_same(run_gpu(gpu, Q, K, V, p, tile, bias=bias, packed=True), ref, label + " (packed bias)")
 
 
 def rand_case(shape, seed, sigma=1.0, q_gain=1.0):
@@ -153,6 +165,31 @@ def test_coarse_and_fine_scales(gpu):
 # ------------------------------------------------------------------------------ bias and mask
 
 
+def packed_layout(bias):
+    """The packed layout as the header defines it, element by element (NumPy indexing only)."""
+    bB, bH, N, _ = bias.shape
+    R = (N + 31) // 32
+    s, rb, cb, a, l, b = np.meshgrid(np.arange(bB * bH), np.arange(R), np.arange(R), np.arange(4),
+                                     np.arange(64), np.arange(4), indexing="ij")
+    row = np.minimum(32 * rb + l % 32, N - 1)
+    col = 32 * cb + 8 * a + 4 * (l // 32) + b
+    flat = bias.reshape(bB * bH, N, N)
+    return np.where(col < N, flat[s, row, np.minimum(col, N - 1)], np.int32(EXCLUDED)).astype(np.int32)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 49, 49), (1, 2, 64, 64), (3, 1, 197, 197), (1, 1, 577, 577)])
+def test_pack_bias_layout(gpu, shape):
+    torch, qf, ctx = gpu
+    rng = np.random.default_rng(shape[2])
+    bias = rng.integers(-(1 << 30), 1 << 30, size=shape).astype(np.int32)
+    want = packed_layout(bias)
+    assert qf.qflash_packed_bias_bytes(*shape[:3]) == want.size * 4
+    got = ctx.pack_bias(torch.from_numpy(bias).to("cuda:0"))
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want.ravel())
+
+
+
 def test_bias_and_exclusion(gpu):
     Q, K, V, sQ, sK, _ = rand_case((4, 3, 49, 32), 43, q_gain=1.5)
     p = oracle.derive_params(sQ, sK, 32)
@@ -209,27 +246,41 @@ def test_table1_workloads(gpu, name):
         check(gpu, wl.Q, wl.K, wl.V, p, tile, bias=wl.bias, label=name)
 
 
+@pytest.mark.parametrize("shape,bias_bh,tile", [
+    ((80, 3, 49, 32), (64, 3), 64),      # four windows per workgroup, 1.25 bias periods
+    ((128, 3, 49, 32), (64, 3), 64),     # whole periods
+    ((20, 2, 197, 64), (8, 2), 64),      # one pair per workgroup, 2.5 periods
+    ((16, 1, 300, 64), (8, 1), 128),     # two query tiles per pair
+    ((8, 1, 1200, 64), (8, 1), 64),      # streamed kernel
+    # last tile more than half full: with a packed bias it runs as a full tile
+    ((4, 2, 120, 64), (1, 2), 64), ((2, 2, 250, 32), (2, 1), 64), ((2, 2, 230, 64), (1, 1), 128),
+    ((3, 2, 33, 32), (1, 1), 64), ((3, 2, 97, 32), (3, 2), 128),
+])
+def test_bias_period_mapping(gpu, shape, bias_bh, tile):
+    """Launches whose bias repeats every 8k units of work take the bias-aware placement of
+    workgroups; the result must not depend on placement."""
+    B, H, N, d = shape
+    Q, K, V, sQ, sK, _ = rand_case(shape, 300 + N)
+    p = oracle.derive_params(sQ, sK, d)
+    rng = np.random.default_rng(N)
+    bias = rng.integers(-4000, 4000, size=bias_bh + (N, N)).astype(np.int32)
+    bias[rng.random(bias.shape) < 0.1] = EXCLUDED
+    check(gpu, Q, K, V, p, tile, bias=bias, label="bias period %s" % (bias_bh,))
+
+
 # ------------------------------------------------------------- per-head constants (Appendix C3)
 
 
-def run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=None):
-    torch, qf, ctx = gpu
-    dev = torch.device("cuda:0")
-    tQ, tK, tV = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (Q, K, V))
-    tO = torch.full(Q.shape, 0x55, dtype=torch.int8, device=dev)
-    tB = torch.from_numpy(np.ascontiguousarray(bias)).to(dev) if bias is not None else None
-    ctx.attention(tQ, tK, tV, tO, [lib_params(qf, p) for p in ps], tile, bias=tB)
-    torch.cuda.synchronize()
-    return tO.cpu().numpy()
+def run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=None, packed=False):
+    return run_gpu(gpu, Q, K, V, list(ps), tile, bias=bias, packed=packed)
 
 
 def check_per_head(gpu, Q, K, V, ps, tile, bias=None, label=""):
     print("per-head case", label, Q.shape, "tile", tile, "bias", bias is not None, flush=True)
     ref = oracle.qflash_attention(Q, K, V, ps, tile, bias=bias)
-    out = run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=bias)
-    bad = np.argwhere(out != ref)
-    assert bad.size == 0, "%s: %d mismatches, first at %s: gpu %d oracle %d" % (
-        label, len(bad), bad[0], out[tuple(bad[0])], ref[tuple(bad[0])])
+    assert_same(run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=bias), ref, label)
+    if bias is not None:
+        assert_same(run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=bias, packed=True), ref, label + " (packed bias)")
 
 
 @pytest.mark.parametrize("shape,tile", [((2, 4, 197, 64), 64), ((3, 5, 49, 32), 64), ((1, 3, 300, 64), 128),
@@ -414,6 +465,9 @@ def test_random_configurations(gpu, seed):
     ref = oracle.qflash_attention(Q, K, V, ps, tile, bias=bias)
     out = run_gpu_per_head(gpu, Q, K, V, ps, tile, bias=bias) if per_head else run_gpu(gpu, Q, K, V, ps, tile, bias=bias)
     assert np.array_equal(out, ref)
+    if bias is not None:
+        out = run_gpu(gpu, Q, K, V, ps, tile, bias=bias, packed=True)
+        assert np.array_equal(out, ref), "packed bias"
 
 
 # ------------------------------------------------------------------------------ ABI behaviour
@@ -521,6 +575,26 @@ def test_error_codes_on_gpu(gpu):
         assert call(par=bad) == qf.ERR["PARAM"], field
     assert lib.qflash_configure(h, 99, 1) == qf.ERR["PARAM"]
     assert lib.qflash_configure(h, qf.CFG_EXP_TABLE, 2) == qf.ERR["PARAM"]
+    # packed bias: sizes, alignment, number of parameter sets
+    assert qf.qflash_packed_bias_bytes(1, 1, 64) == 2 * 2 * 4 * 64 * 16
+    assert qf.qflash_packed_bias_bytes(0, 1, 64) == 0 and qf.qflash_packed_bias_bytes(1, 1, 4097) == 0
+    b32 = torch.zeros((1, 1, 64, 64), dtype=torch.int32, device=dev)
+    pk = torch.zeros(qf.qflash_packed_bias_bytes(1, 1, 64) // 4 + 4, dtype=torch.int32, device=dev)
+    nbytes = ctypes.c_size_t(pk.numel() * 4 - 16)
+    assert lib.qflash_pack_bias(h, ptr(b32), 1, 1, 64, ptr(pk), nbytes, None) == 0
+    assert lib.qflash_pack_bias(h, None, 1, 1, 64, ptr(pk), nbytes, None) == qf.ERR["NULL"]
+    assert lib.qflash_pack_bias(h, ptr(b32), 1, 1, 64, ptr(pk), ctypes.c_size_t(1024), None) == qf.ERR["SHAPE"]
+    assert lib.qflash_pack_bias(h, ptr(b32), 1, 0, 64, ptr(pk), nbytes, None) == qf.ERR["SHAPE"]
+    assert lib.qflash_pack_bias(h, ptr(b32), 1, 1, 64, ctypes.c_void_p(pk.data_ptr() + 4), nbytes, None) == qf.ERR["ALIGN"]
+
+    def call_pk(pkp, n_params=1, H=1):
+        return lib.qflash_attention_packed_bias(h, ptr(t), ptr(t), ptr(t), ptr(o), pkp, 1, 1, 1, H, 64, 64, 64,
+                                                ctypes.byref(p), n_params, None)
+
+    assert call_pk(ptr(pk)) == 0
+    assert call_pk(None) == qf.ERR["NULL"]
+    assert call_pk(ptr(pk), n_params=2) == qf.ERR["PARAM"]
+    assert call_pk(ctypes.c_void_p(pk.data_ptr() + 4)) == qf.ERR["ALIGN"]
     torch.cuda.synchronize()
     # context life cycle
     h2 = qf.qflash_create(0)
