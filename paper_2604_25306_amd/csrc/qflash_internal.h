@@ -37,6 +37,8 @@ struct QflashKernelArgs {
     int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
     int pipelined;           // resident only: K/V tiles are staged one ahead of their use
+    int ring;                // pipelined only: LDS holds two KV tiles (in use / being staged), not the whole sequence
+    int kv_tile;             // KV tile size the plan was made for
     int n_cu;                // compute units of the device if wave priority alternates by dispatch round, else 0
     // weight mode of the launch (uniform over heads): 2 = every head reads its table,
     // 1 = arithmetic with x_shift == 0 for every head, 0 = arithmetic

@@ -20,7 +20,9 @@
 //             of each pair live in LDS (N up to about 1100), every KV tile in a region of its
 //             own.  They are staged either all at once (one barrier, then no barrier in the KV
 //             loop) or tile by tile, one tile ahead of its use, with the next tile's global loads
-//             in flight during the arithmetic and one barrier per tile.
+//             in flight during the arithmetic and one barrier per tile.  Long sequences keep
+//             only two tiles in LDS (the one in use, the one being staged) so that several
+//             smaller workgroups share a compute unit.
 //   stream    one workgroup = 128 query rows; KV tiles are staged per iteration (any N).
 //
 // An additive int32 bias (windowed attention) comes in one of two layouts, each a template variant:
@@ -573,7 +575,10 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     constexpr int KROW = D + 16;
     const int N = a.N;
     const int npad = (N + 31) & ~31;
-    const int VROW = npad + 16;
+    // a.ring: LDS holds two KV tiles (the one in use and the one being staged) instead of the whole
+    // sequence, so that long sequences leave room for a second workgroup on the compute unit.
+    const bool ring = a.ring != 0;
+    const int VROW = (ring ? BC : npad) + 16;
     // A workgroup serves heads_per_wg consecutive (batch, head) pairs when one pair needs only a
     // few wavefronts (windowed attention): wavefront w belongs to pair w / waves_per_head.  Each
     // pair's K and V^T are staged by its own wavefronts; the weight table is shared.
@@ -608,8 +613,9 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int row0 = qt * a.rows_per_wg + (wave - sub * a.waves_per_head) * 32;
     const int i = row0 + li;
 
-    int8_t* sK = smem + tbytes + (size_t)sub * ((size_t)npad * KROW + (size_t)D * VROW);
-    int8_t* sV = sK + (size_t)npad * KROW;
+    const int k_rows = ring ? 2 * BC : npad;                 // K rows held in LDS
+    int8_t* sK = smem + tbytes + (size_t)sub * ((size_t)k_rows * KROW + (size_t)D * VROW);
+    int8_t* sV = sK + (size_t)k_rows * KROW;                // ring: two V^T slots of D x VROW each
 
     const size_t head_off = (size_t)(pair_valid ? bh : 0) * N * D;
     const int8_t* Qh = a.Q + head_off;
@@ -652,20 +658,23 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
         const int rows_t = min(BC, npad - c0);
         const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
         if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {
+            // LDS position of sequence row c0: its own place, or the start of ring slot j % 2
+            const int l0 = ring ? (j & 1) * BC : c0;
             if (__builtin_amdgcn_readfirstlane(tid) < nK) {
-                const int r = c0 + tid / (D / 32), h = tid % (D / 32);
-                const bool ok = r < N;
+                const int rt = tid / (D / 32), h = tid % (D / 32);
+                const bool ok = c0 + rt < N;
                 v4i lo = {pf[0][0], pf[0][1], pf[1][0], pf[1][1]}, hi = {pf[2][0], pf[2][1], pf[3][0], pf[3][1]};
                 if (!ok) lo = hi = v4i{0, 0, 0, 0};
-                *(v4i*)(sK + r * KROW + 32 * h) = lo;
-                *(v4i*)(sK + r * KROW + 32 * h + 16) = hi;
+                *(v4i*)(sK + (l0 + rt) * KROW + 32 * h) = lo;
+                *(v4i*)(sK + (l0 + rt) * KROW + 32 * h + 16) = hi;
             } else {
                 const int iv = tid - nK;
-                const int r0 = c0 + 4 * (iv / (D / 8));
+                const int rt = 4 * (iv / (D / 8));
                 v2i rw[4];
 #pragma unroll
-                for (int b = 0; b < 4; ++b) rw[b] = r0 + b < N ? pf[b] : v2i{0, 0};
-                store_v_4x8(rw, iv % (D / 8), sV, VROW, r0 & ~31, r0 & 31);
+                for (int b = 0; b < 4; ++b) rw[b] = c0 + rt + b < N ? pf[b] : v2i{0, 0};
+                int8_t* sVt = ring ? sV + (size_t)(j & 1) * D * VROW : sV;
+                store_v_4x8(rw, iv % (D / 8), sVt, VROW, (ring ? rt : c0 + rt) & ~31, rt & 31);
             }
         }
     };
@@ -765,8 +774,10 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const bool ragged_as_full = bias_packed && rem > BC - 32;
 #define QF_TILE(FULL_, FIRST_, J_, NV_)                                                                      \
     if (active)                                                                                              \
-    process_tile<D, BC, BIAS, XM, SB, FULL_, FIRST_>(st, qreg, sK + (size_t)(J_) * BC * KROW, KROW,          \
-                                                     sV + (J_) * BC, VROW, NV_, hc.lut_xp,                   \
+    process_tile<D, BC, BIAS, XM, SB, FULL_, FIRST_>(st, qreg,                                               \
+                                                     sK + (size_t)(ring ? (J_) & 1 : (J_)) * BC * KROW, KROW, \
+                                                     ring ? sV + (size_t)((J_) & 1) * D * VROW : sV + (J_) * BC, \
+                                                     VROW, NV_, hc.lut_xp,                                   \
                                                      BIAS ? bias_row + (J_) * (bias_packed ? BC * 32 : BC) : nullptr, \
                                                      (BPRE_OK && (FIRST_)) ? bpre : nullptr,                 \
                                                      c, hc.a_mul, li, g, zb)
@@ -950,11 +961,16 @@ int launch_dbc(const QflashKernelArgs& a, bool resident, size_t lds, int lds_lim
 
 }  // namespace
 
-// LDS bytes of the resident kernel: K and V^T of `heads` heads of N rows and the weight table;
-// 0 if they do not fit.
-static size_t resident_lds_bytes(int N, int d, int heads, int table_bytes, int lds_limit) {
+// LDS bytes of the resident kernel: K and V^T of `heads` heads of N rows (ring: of two KV tiles)
+// and the weight table; 0 if they do not fit.
+// Table size assumed when deciding whether two workgroups with the whole sequence in LDS fit a compute unit.
+constexpr int kRingTableGuess = 32 * 1024;
+
+static size_t resident_lds_bytes(int N, int d, int heads, int table_bytes, int lds_limit, int ring_tile = 0) {
     const size_t npad = (size_t)((N + 31) & ~31);
-    const size_t bytes = (size_t)heads * (npad * (size_t)(d + 16) + (size_t)d * (npad + 16)) + (size_t)table_bytes;
+    const size_t kv = ring_tile ? 2 * ((size_t)ring_tile * (size_t)(d + 16) + (size_t)d * (size_t)(ring_tile + 16))
+                                : npad * (size_t)(d + 16) + (size_t)d * (npad + 16);
+    const size_t bytes = (size_t)heads * kv + (size_t)table_bytes;
     return bytes <= (size_t)lds_limit ? bytes : 0;
 }
 
@@ -962,7 +978,33 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     a->resident = resident_lds_bytes(N, d, 1, 0, lds_limit) != 0;
     a->heads_per_wg = 1;
     a->pipelined = 0;
-    if (a->resident) {
+    a->ring = 0;
+    a->kv_tile = kv_tile;
+    // Long sequences: K and V^T of the whole sequence (plus a weight table) would leave room for
+    // one workgroup per compute unit, or for none.  Where the kernel variant can stage tile by
+    // tile (d = 64, tile 64), LDS holds two tiles only and workgroups are at most 8 wavefronts,
+    // so that two of them share a compute unit.
+    const bool two_fit = resident_lds_bytes(N, d, 1, kRingTableGuess, lds_limit / 2) != 0;
+    if (d == 64 && kv_tile == 64 && N > 256 && !two_fit) {
+        // Workgroups of up to 8 wavefronts (two per compute unit: 128 registers leave four
+        // wavefront slots per SIMD) or of 4 (four per compute unit, one wavefront on every SIMD,
+        // but every wavefront then also stages K/V): whichever gives the busiest compute unit
+        // fewer workgroups to run one after the other.
+        const int nblk = (N + 31) / 32;
+        const int cus = a->n_cu > 0 ? a->n_cu : 256;
+        const int tiles8 = (nblk + 7) / 8, tiles4 = (nblk + 3) / 4;
+        const long long turns8 = ((long long)BH * tiles8 + 2ll * cus - 1) / (2ll * cus);
+        const long long turns4 = ((long long)BH * tiles4 + 4ll * cus - 1) / (4ll * cus);
+        int tiles = turns4 < turns8 ? tiles4 : tiles8;
+        // one staging item per thread and tile needs kv_tile * d / 16 = 256 threads
+        if ((nblk + tiles - 1) / tiles < 4) tiles = tiles8;
+        const int waves = (nblk + tiles - 1) / tiles;       // balanced: 4..8
+        a->resident = 1;
+        a->ring = 1;
+        a->pipelined = 1;
+        a->rows_per_wg = 32 * waves;
+        a->waves_per_head = waves;
+    } else if (a->resident) {
         const int nblk = (N + 31) / 32;
         const int max_waves = N <= 256 ? resident_max_waves<true>() : resident_max_waves<false>();
         const int tiles = (nblk + max_waves - 1) / max_waves;
@@ -1011,8 +1053,8 @@ int qflash_table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds
     const long long io = 4ll * a.heads_per_wg * a.N * d;
     if (io < (long long)table_bytes) return 0;
     // keep two workgroups per CU when the sequence is short enough for that to matter
-    const int budget = a.N <= 256 ? lds_limit / 2 : lds_limit;
-    return resident_lds_bytes(a.N, d, a.heads_per_wg, table_bytes, budget) != 0;
+    const int budget = a.ring ? lds_limit / (16 / a.waves_per_head) : a.N <= 256 ? lds_limit / 2 : lds_limit;
+    return resident_lds_bytes(a.N, d, a.heads_per_wg, table_bytes, budget, a.ring ? a.kv_tile : 0) != 0;
 }
 
 int qflash_launch_build_table(uint8_t* tbl, int n, int n_padded, int x_p, const QflashHeadConsts& a, void* stream) {
@@ -1056,7 +1098,11 @@ int qflash_launch_pack_bias(const int32_t* bias, int slices, int N, int32_t* pac
 
 int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.exp_mode == kExpTable ? a.lut_bytes_max : 0, lds_limit) : 0;
+    if (a.ring && (!a.pipelined || d != 64 || kv_tile != 64 || a.kv_tile != kv_tile || a.heads_per_wg != 1 ||
+                   64 * a.waves_per_head < kv_tile * d / 16))
+        return (int)hipErrorInvalidValue;   // the ring is compiled into the tile-by-tile variants only
+    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.exp_mode == kExpTable ? a.lut_bytes_max : 0,
+                                                       lds_limit, a.ring ? kv_tile : 0) : 0;
     if (a.resident && lds == 0) return (int)hipErrorInvalidValue;
     const int threads = a.resident ? 64 * a.waves_per_head * a.heads_per_wg : kStreamThreads;
     if (d == 64 && kv_tile == 64) return launch_dbc<64, 64>(a, a.resident, lds, lds_limit, threads, st);

@@ -268,6 +268,29 @@ def test_bias_period_mapping(gpu, shape, bias_bh, tile):
     check(gpu, Q, K, V, p, tile, bias=bias, label="bias period %s" % (bias_bh,))
 
 
+@pytest.mark.parametrize("shape,with_bias", [
+    ((2, 3, 331, 64), False),    # shortest sequences that keep two KV tiles in LDS: ragged last tile
+    ((1, 2, 353, 64), True),     # one row into a new row block; bias, plain and packed
+    ((3, 2, 384, 64), False),    # whole tiles only
+    ((40, 13, 400, 64), False),  # enough pairs for the 4-wavefront workgroups
+    ((1, 2, 640, 64), True),
+    ((1, 2, 1089, 64), False),   # beyond what fits LDS as a whole
+    ((1, 1, 2500, 64), False),
+])
+def test_two_tile_ring(gpu, shape, with_bias):
+    """d = 64, kv_tile 64, N > 330 or so: the kernel keeps two KV tiles in LDS and reuses the slots."""
+    B, H, N, d = shape
+    Q, K, V, sQ, sK, _ = rand_case(shape, 700 + N, q_gain=1.3)
+    p = oracle.derive_params(sQ, sK, d)
+    bias = None
+    if with_bias:
+        rng = np.random.default_rng(N)
+        bias = rng.integers(-3000, 3000, size=(1, H, N, N)).astype(np.int32)
+        bias[rng.random(bias.shape) < 0.2] = EXCLUDED
+        bias[0, 0, 7, :] = EXCLUDED
+    check(gpu, Q, K, V, p, 64, bias=bias, label="ring")
+
+
 # ------------------------------------------------------------- per-head constants (Appendix C3)
 
 
