@@ -117,9 +117,12 @@ __global__ __launch_bounds__(256) void qflash_dyn_quantize(const float* q, const
 }  // namespace
 
 int qflash_dynamic_partials(long long n) {
-    // enough workgroups to keep every HBM channel busy; each streams a contiguous-stride share
+    // enough workgroups to keep every HBM channel busy (two per compute unit and tensor); each
+    // streams a grid-strided share
     long long wgs = (n / 4 + 255) / 256;
-    if (wgs > 2048) wgs = 2048;
+    // (every workgroup of the second kernel re-reads all partial maxima of its tensor: with 2048
+    // of them that prologue cost a fifth of the kernel)
+    if (wgs > 512) wgs = 512;
     if (wgs < 1) wgs = 1;
     return (int)wgs;
 }
