@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default=None)
     ap.add_argument("--kv-tile", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None,
+                    help="run the named workload at another batch size (its B; for the windowed "
+                         "workloads: number of windows); the roofline traffic figure is then omitted")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="replay the launches from a captured HIP graph of 50 steps (for workloads so "
@@ -70,7 +73,7 @@ def main():
         sys.exit(1)
     qf.load_library()           # fails loudly when the HIP library is missing
     name = args.workload or HEADLINE
-    wl = make_workload(name, per_head=args.per_head)
+    wl = make_workload(name, batch=args.batch, per_head=args.per_head)
     B, H, N, d = wl.shape
     tile = args.kv_tile or wl.kv_tiles[0]
     if args.per_head:
@@ -84,7 +87,7 @@ def main():
     if args.dynamic:
         # float32 Q, K, V read twice (abs-max, quantise), int8 copies written and read, O written
         from workloads import make_float_qkv
-        floats = make_float_qkv(name)
+        floats = make_float_qkv(name, batch=args.batch)
         io_bytes = (2 * 12 + 3 + 3 + 1) * B * H * N * d
     n_sets = max(1, -(-int(LLC_BYTES * 1.25) // io_bytes))
     src = floats if args.dynamic else (wl.Q, wl.K, wl.V)
@@ -176,7 +179,7 @@ def main():
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.batch is None:
         with open(tpath) as f:
             traffic = json.load(f).get("%s/kv%d%s" % (name, tile, "/dynamic" if args.dynamic else
                                                        "/plain_bias" if bias is not None and packed is None else ""))
