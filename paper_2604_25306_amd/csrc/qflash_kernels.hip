@@ -570,7 +570,7 @@ __device__ __forceinline__ const int32_t* bias_lane_base(const QflashKernelArgs&
 }
 
 template <int D, int BC, int BIAS, bool NARROW, int XM>
-__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : 3) void qflash_fwd_resident(const QflashKernelArgs a) {
+__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : (BC == 64 ? 4 : 3)) void qflash_fwd_resident(const QflashKernelArgs a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
     const int N = a.N;
@@ -636,25 +636,60 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // sequence read row N-1 and are zeroed when written to LDS): straight-line loads are what
     // lets the compiler count exactly which of them a later wait has to cover.
     v2i pf[4], pf0[4];   // tile in flight; tile 0 (prologue only)
+    const int n_full = N / BC, rem = N - n_full * BC;
+    const int tid_ = tid;
+    // A full tile (all BC rows inside the sequence) needs no clamping, its item count is a
+    // compile-time constant and the item of a thread sits at the same offset in every tile, so
+    // its four addresses are a uniform base (head, tile) plus a per-thread constant plus a
+    // multiple of a uniform step: a dozen instructions where the general computation (the last
+    // tile of a ragged sequence) takes fifty.
+    constexpr int NKF = BC * (D / 32);    // K items of a full tile
+    // (Both lambdas derive their addresses from a copy of the thread index that the compiler
+    // cannot see through: otherwise it hoists every loop-invariant piece of address arithmetic
+    // out of the KV loop and pays for it with registers held across all the tile code.)
     auto load_tile = [&](int j, v2i* pf) {
         const int c0 = j * BC;
-        const int rows_t = min(BC, npad - c0);
+        int tid = tid_;
+        asm volatile("" : "+v"(tid));
+        const bool full = j < n_full;                           // uniform
+        const int rows_t = full ? BC : min(BC, npad - c0);
         const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
         if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {   // whole wavefronts, nK + nV is a multiple of 64
-            const bool is_k = tid < nK;
-            const int iv = tid - nK;
-            const int8_t* base = is_k ? Kh : Vh;
-            const int row = c0 + (is_k ? tid / (D / 32) : 4 * (iv / (D / 8)));
-            const int col = is_k ? 32 * (tid % (D / 32)) : 8 * (iv % (D / 8));
+            // Only the addresses differ between the two kinds of tile; the four loads themselves
+            // are one sequence on every path (loads in different branches would end in different
+            // registers, and the copies that reconcile them would have to wait for the data).
+            // (global address space spelled out: through the merge of the two computations the
+            // compiler would otherwise lose it and fall back to generic-address loads)
+            typedef const __attribute__((address_space(1))) int8_t* gptr;
+            gptr p[4];
+            if (full) {
+                const bool is_k = __builtin_amdgcn_readfirstlane(tid) < NKF;        // uniform
+                const unsigned iv = (unsigned)(tid - NKF);
+                const unsigned off = is_k ? 32u * (unsigned)tid : 4u * (iv / (D / 8)) * D + 8u * (iv % (D / 8));
+                gptr base = (gptr)(is_k ? Kh : Vh) + (size_t)c0 * D + off;
+                const int step = is_k ? 8 : D;
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int rb = min(is_k ? row : row + b, N - 1);
-                pf[b] = *(const v2i*)(base + (size_t)rb * D + col + (is_k ? 8 * b : 0));
+                for (int b = 0; b < 4; ++b) p[b] = base + b * step;
+            } else {
+                const bool is_k = tid < nK;
+                const int iv = tid - nK;
+                gptr base = (gptr)(is_k ? Kh : Vh);
+                const int row = c0 + (is_k ? tid / (D / 32) : 4 * (iv / (D / 8)));
+                const int col = is_k ? 32 * (tid % (D / 32)) : 8 * (iv % (D / 8));
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int rb = min(is_k ? row : row + b, N - 1);
+                    p[b] = base + (size_t)rb * D + col + (is_k ? 8 * b : 0);
+                }
             }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) pf[b] = *(const __attribute__((address_space(1))) v2i*)p[b];
         }
     };
     auto write_tile = [&](int j, const v2i* pf) {
         const int c0 = j * BC;
+        int tid = tid_;
+        asm volatile("" : "+v"(tid));
         const int rows_t = min(BC, npad - c0);
         const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
         if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {
@@ -662,9 +697,8 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
             const int l0 = ring ? (j & 1) * BC : c0;
             if (__builtin_amdgcn_readfirstlane(tid) < nK) {
                 const int rt = tid / (D / 32), h = tid % (D / 32);
-                const bool ok = c0 + rt < N;
                 v4i lo = {pf[0][0], pf[0][1], pf[1][0], pf[1][1]}, hi = {pf[2][0], pf[2][1], pf[3][0], pf[3][1]};
-                if (!ok) lo = hi = v4i{0, 0, 0, 0};
+                if (!(c0 + rt < N)) lo = hi = v4i{0, 0, 0, 0};
                 *(v4i*)(sK + (l0 + rt) * KROW + 32 * h) = lo;
                 *(v4i*)(sK + (l0 + rt) * KROW + 32 * h + 16) = hi;
             } else {
@@ -681,9 +715,9 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // Order of the prologue: the loads with the longest way to go first (K/V tile 0 from HBM), then
     // the query rows, then the table (L2); all of them are in flight together and the first wait
     // covers them all.
-    if (pipelined) {
+    if (pipelined) {                        // N > BC: tile 0 is a full one
         load_tile(0, pf0);
-        if (n_tiles > 1) load_tile(1, pf);
+        load_tile(1, pf);
     }
     // ---- this lane's query row.  Lanes beyond the sequence read the last row instead (their
     //      results are never stored and rows do not interact), which keeps the loads free of branches.
@@ -767,7 +801,6 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
 
     // First tile (no rescale), the remaining full tiles as one straight-line loop body, then the
     // ragged tile if the sequence does not end on a tile boundary.
-    const int n_full = N / BC, rem = N - n_full * BC;
     // With a packed bias the keys beyond the sequence carry the exclusion mark (and K, V are zero
     // there), so a last tile whose every 32-key block exists in the packed layout runs the
     // straight-line code of a full tile instead of testing each group of keys.
