@@ -78,6 +78,7 @@ def main():
     tile = args.kv_tile or wl.kv_tiles[0]
     if args.per_head:
         params = [qf.qflash_params_from_scales(wl.sQ[h], wl.sK[h], wl.sV[h], d) for h in range(H)]
+        params_c = qf.params_array(params)          # built once: the timed loop only passes it on
     else:
         params = qf.qflash_params_from_scales(wl.sQ, wl.sK, wl.sV, d)
     dev = torch.device("cuda:0")
@@ -110,9 +111,10 @@ def main():
         if args.dynamic:
             ctx.attention_dynamic(q, k, v, o, tile, ws)
         elif packed is not None:
-            ctx.attention_packed_bias(q, k, v, o, params, tile, packed, bias.shape[0], bias.shape[1])
+            ctx.attention_packed_bias(q, k, v, o, params_c if args.per_head else params, tile, packed,
+                                      bias.shape[0], bias.shape[1])
         else:
-            ctx.attention(q, k, v, o, params, tile, bias=bias)
+            ctx.attention(q, k, v, o, params_c if args.per_head else params, tile, bias=bias)
 
     GRAPH_STEPS = 50
     graphs = {}

@@ -161,14 +161,20 @@ def qflash_attention(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, b
         raise QFlashError(rc, "qflash_attention")
 
 
+def params_array(params):
+    """A C array of ``QFlashParams`` from a sequence of them: what the per-head entry points take.
+    Callers in a loop build it once and pass it instead of the sequence."""
+    params = list(params)
+    return (QFlashParams * len(params))(*params)
+
+
 def qflash_attention_per_head(ctx: int, Q, K, V, O, params, kv_tile: int, bias=None,
                               stream: Optional[int] = None) -> None:
-    """The same with one ``QFlashParams`` per head (a sequence of H of them)."""
+    """The same with one ``QFlashParams`` per head (a sequence of H of them, or ``params_array`` of it)."""
     args, st = _marshal(Q, K, V, O, bias, stream)
-    params = list(params)
-    if len(params) != args[8]:
+    arr = params if isinstance(params, ctypes.Array) else params_array(params)
+    if len(arr) != args[8]:
         raise ValueError("need one QFlashParams per head")
-    arr = (QFlashParams * len(params))(*params)
     rc = load_library().qflash_attention_per_head(
         ctypes.c_void_p(ctx), *args, int(kv_tile), ctypes.cast(arr, ctypes.POINTER(QFlashParams)), st)
     if rc != 0:
@@ -211,8 +217,8 @@ def qflash_attention_packed_bias(ctx: int, Q, K, V, O, params, kv_tile: int, pac
     if isinstance(params, QFlashParams):
         pp, n_p = ctypes.byref(params), 1
     else:
-        params = list(params)
-        pp, n_p = ctypes.cast((QFlashParams * len(params))(*params), ctypes.POINTER(QFlashParams)), len(params)
+        arr = params if isinstance(params, ctypes.Array) else params_array(params)
+        pp, n_p = ctypes.cast(arr, ctypes.POINTER(QFlashParams)), len(arr)
     rc = load_library().qflash_attention_packed_bias(
         ctypes.c_void_p(ctx), args[0], args[1], args[2], args[3], _ptr(packed), int(bias_B), int(bias_H),
         args[7], args[8], args[9], args[10], int(kv_tile), pp, n_p, st)
