@@ -635,7 +635,10 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     // V; either way four 8-byte loads, issued without any branch around them (rows beyond the
     // sequence read row N-1 and are zeroed when written to LDS): straight-line loads are what
     // lets the compiler count exactly which of them a later wait has to cover.
-    v2i pf[4], pf0[4];   // tile in flight; tile 0 (prologue only)
+    // kv_tile 128 has twice the items: there every staging thread takes one K item and one V item
+    // (256 threads, i.e. the first four wavefronts, stage a whole tile whatever the workgroup size).
+    constexpr int PASSES = BC == 128 ? 2 : 1;
+    v2i pf[4 * PASSES], pf0[4 * PASSES];   // tile in flight; tile 0 (prologue only)
     const int n_full = N / BC, rem = N - n_full * BC;
     const int tid_ = tid;
     // A full tile (all BC rows inside the sequence) needs no clamping, its item count is a
@@ -654,13 +657,39 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
         const bool full = j < n_full;                           // uniform
         const int rows_t = full ? BC : min(BC, npad - c0);
         const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
+        typedef const __attribute__((address_space(1))) int8_t* gptr;
+        if constexpr (PASSES == 2) {
+            // nK == nV (d = 64): thread t < nK takes K item t and V item t
+            if (__builtin_amdgcn_readfirstlane(tid) < nK) {
+                gptr p[8];
+                const unsigned vrow = 4u * ((unsigned)tid / (D / 8)), vcol = 8u * ((unsigned)tid % (D / 8));
+                if (full) {
+                    gptr bk = (gptr)Kh + (size_t)c0 * D + 32u * (unsigned)tid;
+                    gptr bv = (gptr)Vh + (size_t)c0 * D + (vrow * D + vcol);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        p[b] = bk + 8 * b;
+                        p[4 + b] = bv + D * b;
+                    }
+                } else {
+                    const int krow = min(c0 + tid / (D / 32), N - 1);
+                    gptr bk = (gptr)Kh + (size_t)krow * D + 32 * (tid % (D / 32));
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        p[b] = bk + 8 * b;
+                        p[4 + b] = (gptr)Vh + (size_t)min(c0 + (int)vrow + b, N - 1) * D + vcol;
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < 8; ++b) pf[b] = *(const __attribute__((address_space(1))) v2i*)p[b];
+            }
+        } else
         if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {   // whole wavefronts, nK + nV is a multiple of 64
             // Only the addresses differ between the two kinds of tile; the four loads themselves
             // are one sequence on every path (loads in different branches would end in different
             // registers, and the copies that reconcile them would have to wait for the data).
             // (global address space spelled out: through the merge of the two computations the
             // compiler would otherwise lose it and fall back to generic-address loads)
-            typedef const __attribute__((address_space(1))) int8_t* gptr;
             gptr p[4];
             if (full) {
                 const bool is_k = __builtin_amdgcn_readfirstlane(tid) < NKF;        // uniform
@@ -692,6 +721,26 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
         asm volatile("" : "+v"(tid));
         const int rows_t = min(BC, npad - c0);
         const int nK = rows_t * (D / 32), nV = (rows_t / 4) * (D / 8);
+        if constexpr (PASSES == 2) {
+            if (__builtin_amdgcn_readfirstlane(tid) < nK) {
+                const int l0 = ring ? (j & 1) * BC : c0;
+                {
+                    const int rt = tid / (D / 32), h = tid % (D / 32);
+                    v4i lo = {pf[0][0], pf[0][1], pf[1][0], pf[1][1]}, hi = {pf[2][0], pf[2][1], pf[3][0], pf[3][1]};
+                    if (!(c0 + rt < N)) lo = hi = v4i{0, 0, 0, 0};
+                    *(v4i*)(sK + (l0 + rt) * KROW + 32 * h) = lo;
+                    *(v4i*)(sK + (l0 + rt) * KROW + 32 * h + 16) = hi;
+                }
+                {
+                    const int rt = 4 * (tid / (D / 8));
+                    v2i rw[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) rw[b] = c0 + rt + b < N ? pf[4 + b] : v2i{0, 0};
+                    int8_t* sVt = ring ? sV + (size_t)(j & 1) * D * VROW : sV;
+                    store_v_4x8(rw, tid % (D / 8), sVt, VROW, (ring ? rt : c0 + rt) & ~31, rt & 31);
+                }
+            }
+        } else
         if (__builtin_amdgcn_readfirstlane(tid) < nK + nV) {
             // LDS position of sequence row c0: its own place, or the start of ring slot j % 2
             const int l0 = ring ? (j & 1) * BC : c0;
@@ -1018,20 +1067,26 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     // tile (d = 64, tile 64), LDS holds two tiles only and workgroups are at most 8 wavefronts,
     // so that two of them share a compute unit.
     const bool two_fit = resident_lds_bytes(N, d, 1, kRingTableGuess, lds_limit / 2) != 0;
-    if (d == 64 && kv_tile == 64 && N > 256 && !two_fit) {
-        // Workgroups of up to 8 wavefronts (two per compute unit: 128 registers leave four
-        // wavefront slots per SIMD) or of 4 (four per compute unit, one wavefront on every SIMD,
-        // but every wavefront then also stages K/V): whichever gives the busiest compute unit
-        // fewer workgroups to run one after the other.
+    if (d == 64 && N > 256 && (kv_tile == 128 || !two_fit)) {
         const int nblk = (N + 31) / 32;
         const int cus = a->n_cu > 0 ? a->n_cu : 256;
-        const int tiles8 = (nblk + 7) / 8, tiles4 = (nblk + 3) / 4;
-        const long long turns8 = ((long long)BH * tiles8 + 2ll * cus - 1) / (2ll * cus);
-        const long long turns4 = ((long long)BH * tiles4 + 4ll * cus - 1) / (4ll * cus);
-        int tiles = turns4 < turns8 ? tiles4 : tiles8;
-        // one staging item per thread and tile needs kv_tile * d / 16 = 256 threads
-        if ((nblk + tiles - 1) / tiles < 4) tiles = tiles8;
-        const int waves = (nblk + tiles - 1) / tiles;       // balanced: 4..8
+        int waves;
+        if (kv_tile == 128) {
+            // 160-odd registers leave three wavefront slots per SIMD: three workgroups of four
+            // wavefronts (which is also what stages a tile: 256 threads, two items each)
+            waves = 4;
+        } else {
+            // Workgroups of up to 8 wavefronts (two per compute unit: 128 registers leave four
+            // wavefront slots per SIMD) or of 4 (four per compute unit, one wavefront on every SIMD,
+            // but every wavefront then also stages K/V): whichever gives the busiest compute unit
+            // fewer workgroups to run one after the other.
+            const int tiles8 = (nblk + 7) / 8, tiles4 = (nblk + 3) / 4;
+            const long long turns8 = ((long long)BH * tiles8 + 2ll * cus - 1) / (2ll * cus);
+            const long long turns4 = ((long long)BH * tiles4 + 4ll * cus - 1) / (4ll * cus);
+            int tiles = turns4 < turns8 ? tiles4 : tiles8;
+            if ((nblk + tiles - 1) / tiles < 4) tiles = tiles8;   // staging needs 256 threads
+            waves = (nblk + tiles - 1) / tiles;                   // balanced: 4..8
+        }
         a->resident = 1;
         a->ring = 1;
         a->pipelined = 1;
@@ -1052,10 +1107,9 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
             while (hp > 1 && resident_lds_bytes(N, d, hp, 0, lds_limit / 4) == 0) --hp;
             a->heads_per_wg = hp;
         }
-        // Tile-by-tile staging needs a second KV tile to overlap with and one staging item per
-        // thread: 32-byte pieces of K plus 4x8 blocks of V of one tile.
-        const int items = kv_tile * d / 16;
-        a->pipelined = a->heads_per_wg == 1 && N > kv_tile && items <= 64 * waves;
+        // Tile-by-tile staging needs a second KV tile to overlap with and 256 staging threads
+        // (32-byte pieces of K plus 4x8 blocks of V of one tile, one or two items per thread).
+        a->pipelined = a->heads_per_wg == 1 && N > kv_tile && waves >= 4;
     } else {
         a->rows_per_wg = kStreamRows;
         a->waves_per_head = kStreamWaves;
@@ -1086,7 +1140,7 @@ int qflash_table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds
     const long long io = 4ll * a.heads_per_wg * a.N * d;
     if (io < (long long)table_bytes) return 0;
     // keep two workgroups per CU when the sequence is short enough for that to matter
-    const int budget = a.ring ? lds_limit / (16 / a.waves_per_head) : a.N <= 256 ? lds_limit / 2 : lds_limit;
+    const int budget = (a.ring || a.N <= 256) ? lds_limit / 2 : lds_limit;
     return resident_lds_bytes(a.N, d, a.heads_per_wg, table_bytes, budget, a.ring ? a.kv_tile : 0) != 0;
 }
 
@@ -1131,8 +1185,7 @@ int qflash_launch_pack_bias(const int32_t* bias, int slices, int N, int32_t* pac
 
 int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
-    if (a.ring && (!a.pipelined || d != 64 || kv_tile != 64 || a.kv_tile != kv_tile || a.heads_per_wg != 1 ||
-                   64 * a.waves_per_head < kv_tile * d / 16))
+    if (a.ring && (!a.pipelined || d != 64 || a.kv_tile != kv_tile || a.heads_per_wg != 1 || a.waves_per_head < 4))
         return (int)hipErrorInvalidValue;   // the ring is compiled into the tile-by-tile variants only
     const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.exp_mode == kExpTable ? a.lut_bytes_max : 0,
                                                        lds_limit, a.ring ? kv_tile : 0) : 0;

@@ -276,9 +276,13 @@ def test_bias_period_mapping(gpu, shape, bias_bh, tile):
     ((1, 2, 640, 64), True),
     ((1, 2, 1089, 64), False),   # beyond what fits LDS as a whole
     ((1, 1, 2500, 64), False),
+    ((2, 2, 257, 64), True),     # shortest sequence of the kv_tile 128 ring: 2 tiles, the second one row
+    ((2, 2, 300, 64), False),
 ])
-def test_two_tile_ring(gpu, shape, with_bias):
-    """d = 64, kv_tile 64, N > 330 or so: the kernel keeps two KV tiles in LDS and reuses the slots."""
+@pytest.mark.parametrize("tile", [64, 128])
+def test_two_tile_ring(gpu, shape, with_bias, tile):
+    """d = 64 and N > 330 or so (kv_tile 64) or N > 256 (kv_tile 128): the kernel keeps two KV tiles
+    in LDS and reuses the slots; with kv_tile 128 every staging thread carries two items."""
     B, H, N, d = shape
     Q, K, V, sQ, sK, _ = rand_case(shape, 700 + N, q_gain=1.3)
     p = oracle.derive_params(sQ, sK, d)
@@ -288,7 +292,7 @@ def test_two_tile_ring(gpu, shape, with_bias):
         bias = rng.integers(-3000, 3000, size=(1, H, N, N)).astype(np.int32)
         bias[rng.random(bias.shape) < 0.2] = EXCLUDED
         bias[0, 0, 7, :] = EXCLUDED
-    check(gpu, Q, K, V, p, 64, bias=bias, label="ring")
+    check(gpu, Q, K, V, p, tile, bias=bias, label="ring")
 
 
 # ------------------------------------------------------------- per-head constants (Appendix C3)
