@@ -571,6 +571,40 @@ def test_table_cache_many_constants_and_streams(gpu):
     assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64), oracle.qflash_attention(Q, K, V, p, 64))
 
 
+def test_concurrent_host_threads(gpu):
+    """Several host threads call one context at once, each on its own stream and with its own
+    constants (the table cache is filled concurrently); every result equals the oracle's."""
+    import threading
+    torch, qf, _ = gpu
+    ctx = qf.Context(0)
+    shape = (2, 3, 150, 64)
+    rng = np.random.default_rng(99)
+    Q, K, V = (rng.integers(-127, 128, size=shape).astype(np.int8) for _ in range(3))
+    n_threads, rounds = 4, 6
+    params = [[oracle.derive_params(0.02 + 0.003 * (t * rounds + r), 0.05, 64) for r in range(rounds)]
+              for t in range(n_threads)]
+    refs = [[oracle.qflash_attention(Q, K, V, p, 64) for p in row] for row in params]
+    errors = []
+
+    def worker(t):
+        try:
+            s = torch.cuda.Stream()
+            for r in range(rounds):
+                out = run_gpu((torch, qf, ctx), Q, K, V, params[t][r], 64, stream=s.cuda_stream)
+                if not np.array_equal(out, refs[t][r]):
+                    errors.append((t, r))
+        except Exception as e:          # noqa: BLE001 - reported below
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    ctx.close()
+    assert not errors, errors
+
+
 def test_error_codes_on_gpu(gpu):
     torch, qf, ctx = gpu
     lib = qf.load_library()
