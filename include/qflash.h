@@ -209,6 +209,35 @@ int qflash_attention_dynamic(qflash_ctx* ctx,
                              void* hip_stream);
 
 /*
+ * How a call would be laid out on the GPU (host only; nothing is enqueued and no GPU is touched
+ * when ctx is NULL, in which case an MI355X is assumed: 256 compute units, 160 KiB of LDS per
+ * workgroup).  For callers who want to know the occupancy of a shape, and for tests of the host
+ * logic: the work decomposition of Algorithm 1 over (batch, head, query block) is the library's
+ * own choice and does not change a single output bit.
+ *
+ *   bias_B, bias_H   extents of the bias the call would be given, or 0, 0 for none.
+ *   kernel           0: KV tiles streamed through LDS, 128 query rows per workgroup;
+ *                    1: K and V of a (batch, head) pair resident in LDS; 2: two KV tiles in LDS.
+ *   pairs_per_workgroup, wavefronts_per_pair, query_blocks (workgroups a pair is split over),
+ *   units (pieces of work = workgroups that have rows), workgroups (launched; a few may be idle),
+ *   tile_by_tile (1: KV tiles staged one ahead of their use), bias_period_units (0, or the number of
+ *   units after which the bias slices repeat and by which workgroups are dealt to the 8 XCDs).
+ * qflash_plan_unit: the unit that workgroup `workgroup` of such a launch takes, or -1 if it is one
+ * of the idle ones (or out of range).  Every unit in [0, units) is taken by exactly one workgroup.
+ * Errors: NULL, CTX, SHAPE, TILE.
+ */
+typedef struct {
+    int32_t kernel, pairs_per_workgroup, wavefronts_per_pair, query_blocks;
+    int32_t units, workgroups, tile_by_tile, bias_period_units;
+    int32_t units_per_xcd, reserved[3];
+} qflash_plan_info;
+
+int qflash_plan_query(qflash_ctx* ctx /* or NULL */, int B, int H, int N, int d, int kv_tile,
+                      int bias_B, int bias_H, qflash_plan_info* out);
+
+int qflash_plan_unit(const qflash_plan_info* plan, int workgroup);
+
+/*
  * Destroy a context.  NULL is accepted (returns QFLASH_OK).  Destroying a context twice, or a
  * pointer that never was a context, returns QFLASH_ERR_CTX and touches nothing.
  */

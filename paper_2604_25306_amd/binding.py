@@ -17,6 +17,7 @@ ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, 
 EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
            "qflash_attention_per_head", "qflash_dynamic_workspace_bytes", "qflash_attention_dynamic",
            "qflash_packed_bias_bytes", "qflash_pack_bias", "qflash_attention_packed_bias",
+           "qflash_plan_query", "qflash_plan_unit",
            "qflash_destroy", "qflash_strerror"]
 
 MAX_PARAM_HEADS = 64
@@ -46,6 +47,13 @@ class DynamicInfo(ctypes.Structure):
     """Mirror of ``qflash_dynamic_info`` (what the dynamic entry point reports, in device memory)."""
     _fields_ = [("sQ", ctypes.c_double), ("sK", ctypes.c_double), ("sV", ctypes.c_double),
                 ("params", QFlashParams), ("status", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class PlanInfo(ctypes.Structure):
+    """Mirror of ``qflash_plan_info`` (how a call would be laid out on the GPU)."""
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "kernel", "pairs_per_workgroup", "wavefronts_per_pair", "query_blocks", "units", "workgroups",
+        "tile_by_tile", "bias_period_units", "units_per_xcd")] + [("reserved", ctypes.c_int32 * 3)]
 
 
 def library_path() -> str:
@@ -82,6 +90,10 @@ def load_library():
         lib.qflash_pack_bias.argtypes = [vp, vp, ci, ci, ci, vp, ctypes.c_size_t, vp]
         lib.qflash_attention_packed_bias.restype = ci
         lib.qflash_attention_packed_bias.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, ci, vp]
+        lib.qflash_plan_query.restype = ci
+        lib.qflash_plan_query.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(PlanInfo)]
+        lib.qflash_plan_unit.restype = ci
+        lib.qflash_plan_unit.argtypes = [ctypes.POINTER(PlanInfo), ci]
         lib.qflash_configure.restype = ci
         lib.qflash_configure.argtypes = [vp, ci, ci]
         lib.qflash_destroy.restype = ci
@@ -224,6 +236,21 @@ def qflash_attention_packed_bias(ctx: int, Q, K, V, O, params, kv_tile: int, pac
         args[7], args[8], args[9], args[10], int(kv_tile), pp, n_p, st)
     if rc != 0:
         raise QFlashError(rc, "qflash_attention_packed_bias")
+
+
+def qflash_plan_query(ctx: Optional[int], B: int, H: int, N: int, d: int, kv_tile: int,
+                      bias_B: int = 0, bias_H: int = 0) -> PlanInfo:
+    """The launch plan of such a call (host only; ``ctx`` None assumes an MI355X)."""
+    info = PlanInfo()
+    rc = load_library().qflash_plan_query(ctypes.c_void_p(ctx), int(B), int(H), int(N), int(d), int(kv_tile),
+                                          int(bias_B), int(bias_H), ctypes.byref(info))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_plan_query")
+    return info
+
+
+def qflash_plan_unit(plan: PlanInfo, workgroup: int) -> int:
+    return int(load_library().qflash_plan_unit(ctypes.byref(plan), int(workgroup)))
 
 
 def qflash_dynamic_workspace_bytes(B: int, H: int, N: int, d: int) -> int:

@@ -258,6 +258,50 @@ extern "C" int qflash_attention_per_head(qflash_ctx* ctx, const int8_t* Q, const
     return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, true, hip_stream);
 }
 
+extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, int kv_tile, int bias_B,
+                                 int bias_H, qflash_plan_info* out) {
+    if (!out) return QFLASH_ERR_NULL;
+    int lds_limit = 160 * 1024, n_cu = 256;
+    if (ctx) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+        lds_limit = ctx->lds_limit;
+        n_cu = ctx->n_cu;
+    }
+    if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
+    if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
+    if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+    if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
+    const bool has_bias = bias_B != 0 || bias_H != 0;
+    if (has_bias && (bias_B < 1 || bias_H < 1)) return QFLASH_ERR_SHAPE;
+    QflashKernelArgs a;
+    std::memset(&a, 0, sizeof a);
+    static const int32_t some_bias = 0;
+    a.bias = has_bias ? &some_bias : nullptr;    // the plan only asks whether there is one
+    a.bias_B = has_bias ? bias_B : 1;
+    a.bias_H = has_bias ? bias_H : 1;
+    a.B = B; a.H = H; a.N = N;
+    a.n_cu = n_cu;
+    if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
+    std::memset(out, 0, sizeof *out);
+    out->kernel = !a.resident ? 0 : a.ring ? 2 : 1;
+    out->pairs_per_workgroup = a.heads_per_wg;
+    out->wavefronts_per_pair = a.waves_per_head;
+    out->query_blocks = a.n_qtiles;
+    out->units = a.n_units;
+    out->workgroups = 8 * a.units_per_xcd;
+    out->tile_by_tile = a.resident && a.pipelined && d == 64 && (kv_tile == 64 || N > 256) ? 1 : 0;
+    out->bias_period_units = a.xcd_period;
+    out->units_per_xcd = a.units_per_xcd;
+    return QFLASH_OK;
+}
+
+extern "C" int qflash_plan_unit(const qflash_plan_info* plan, int workgroup) {
+    if (!plan || workgroup < 0 || workgroup >= plan->workgroups) return -1;
+    const int unit = qflash_unit_of_workgroup(workgroup, plan->units_per_xcd, plan->bias_period_units);
+    return unit < plan->units ? unit : -1;
+}
+
 extern "C" size_t qflash_packed_bias_bytes(int bias_B, int bias_H, int N) {
     if (bias_B < 1 || bias_H < 1 || N < 1 || N > QFLASH_MAX_N) return 0;
     if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return 0;

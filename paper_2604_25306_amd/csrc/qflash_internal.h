@@ -51,6 +51,24 @@ struct QflashKernelArgs {
     QflashHeadConsts hc[kQflashMaxParamHeads];
 };
 
+// Which unit of work a workgroup takes (host and device: the kernels use it, qflash_plan_unit
+// reports it).  Consecutive workgroup indices go to consecutive XCDs (each with its own L2), so XCD
+// x = wg % 8 takes the units [x*units_per_xcd, (x+1)*units_per_xcd): neighbouring heads share an
+// L2.  With a bias whose slices repeat every xcd_period units (windowed attention: the same windows
+// in every image) XCD x instead takes the x-th eighth of every period, so that each L2 only ever
+// sees an eighth of the bias.  The result may be >= n_units: such a workgroup has nothing to do.
+#if defined(__HIPCC__)
+#define QF_UNIT_HD __host__ __device__
+#else
+#define QF_UNIT_HD
+#endif
+QF_UNIT_HD inline int qflash_unit_of_workgroup(int wg, int units_per_xcd, int xcd_period) {
+    const int x = wg & 7, k = wg >> 3;
+    if (xcd_period == 0) return x * units_per_xcd + k;
+    const int q = xcd_period >> 3;
+    return (k / q) * xcd_period + x * q + k % q;
+}
+
 // Enqueue the forward kernel for head size d (32|64), KV tile (64|128).  Returns a hipError_t value.
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 

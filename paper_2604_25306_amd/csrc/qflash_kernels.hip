@@ -540,18 +540,6 @@ extern __shared__ __align__(16) int8_t smem[];
 template <bool NARROW>
 constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
 
-// Which unit of work a workgroup takes.  Consecutive workgroup indices go to consecutive XCDs
-// (each with its own L2), so XCD x = wg % 8 takes the units [x*units_per_xcd, (x+1)*units_per_xcd):
-// neighbouring heads share an L2.  With a bias whose slices repeat every xcd_period units (windowed
-// attention: the same windows in every image) XCD x instead takes the x-th eighth of every period,
-// so that each L2 only ever sees an eighth of the bias.
-__device__ __forceinline__ int unit_of_workgroup(const QflashKernelArgs& a, int wg) {
-    const int x = wg & 7, k = wg >> 3;
-    if (a.xcd_period == 0) return x * a.units_per_xcd + k;
-    const int q = a.xcd_period >> 3;
-    return (k / q) * a.xcd_period + x * q + k % q;
-}
-
 // Where this lane's bias values start.  Plain layout [bias_B,bias_H,N,N]: the lane's row (lanes
 // beyond the sequence read row 0; their results are never stored).  Packed layout
 // [bias_B*bias_H][ceil(N/32) row blocks][ceil(N/32) column blocks][4 groups][64 lanes][4]: the
@@ -587,7 +575,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int tbytes = XM == kExpTable ? a.lut_bytes_max : 0;   // LDS reserved for the table
 
     const int wg = blockIdx.x;
-    const int unit = unit_of_workgroup(a, wg);
+    const int unit = qflash_unit_of_workgroup(wg, a.units_per_xcd, a.xcd_period);
     if (unit >= a.n_units) return;
     // Workgroups are handed out in index order, one per compute unit and round.  In a launch of
     // only a few rounds, alternating the wave priority by round puts a newcomer ahead of the older
@@ -916,7 +904,7 @@ __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const Qflash
     __shared__ __align__(16) int8_t sV[D * VROW];
 
     const int wg = blockIdx.x;
-    const int unit = unit_of_workgroup(a, wg);
+    const int unit = qflash_unit_of_workgroup(wg, a.units_per_xcd, a.xcd_period);
     if (unit >= a.n_units) return;
     const int qt = unit % a.n_qtiles;
     const int bh = unit / a.n_qtiles;
@@ -1120,7 +1108,7 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     if (units >= (1ll << 30)) return -1;
     a->n_units = (int)units;
     a->units_per_xcd = (a->n_units + 7) / 8;
-    // Bias slices repeat every bias_B * H pairs: see unit_of_workgroup.
+    // Bias slices repeat every bias_B * H pairs: see qflash_unit_of_workgroup.
     a->xcd_period = 0;
     if (a->bias) {
         const long long pairs = (long long)a->bias_B * a->H;

@@ -102,3 +102,63 @@ def test_context_errors_without_gpu(lib):
     assert rc == qf.ERR["DEVICE"] and not h.value
     assert lib.qflash_configure(None, qf.CFG_EXP_TABLE, 1) == qf.ERR["NULL"]
     assert lib.qflash_configure(bogus, qf.CFG_EXP_TABLE, 1) == qf.ERR["CTX"]
+
+
+def _units_taken(plan):
+    return [qf.qflash_plan_unit(plan, wg) for wg in range(plan.workgroups)]
+
+
+def test_plan_covers_every_unit_exactly_once(lib):
+    """Whatever the decomposition, the workgroups of a launch take every unit of work exactly once
+    (idle workgroups report -1): shapes of every kernel family, with and without the bias-period
+    placement, whole and partial periods."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    cases = [(64, 12, 197, 64, 64, 0, 0), (32, 12, 577, 64, 64, 0, 0), (32, 12, 577, 64, 128, 0, 0),
+             (16, 16, 577, 64, 64, 0, 0), (4096, 3, 49, 32, 64, 64, 3), (80, 3, 49, 32, 64, 64, 3),
+             (20, 2, 197, 64, 64, 8, 2), (16, 1, 300, 64, 128, 8, 1), (8, 1, 1200, 64, 64, 8, 1),
+             (1, 1, 4096, 32, 128, 0, 0), (1, 1, 1, 32, 64, 0, 0), (3, 5, 33, 64, 64, 3, 1)]
+    for _ in range(60):
+        B, H = int(rng.integers(1, 300)), int(rng.integers(1, 25))
+        N = int(rng.choice([rng.integers(1, 65), rng.integers(65, 400), rng.integers(400, 4097)]))
+        d, tile = int(rng.choice([32, 64])), int(rng.choice([64, 128]))
+        if B * H * N * d >= 1 << 31:
+            continue
+        bB, bH = (0, 0) if rng.integers(0, 2) else (int(rng.choice([1, 2, 8, 16, 64, B])), int(rng.choice([1, H])))
+        cases.append((B, H, N, d, tile, bB, bH))
+    for c in cases:
+        plan = qf.qflash_plan_query(None, *c)
+        taken = [u for u in _units_taken(plan) if u >= 0]
+        assert sorted(taken) == list(range(plan.units)), c
+        assert plan.workgroups % 8 == 0 and plan.workgroups >= plan.units, c
+        assert plan.bias_period_units % 8 == 0, c
+        pairs = c[0] * c[1]
+        if plan.pairs_per_workgroup > 1:
+            assert plan.query_blocks == 1 and plan.units == -(-pairs // plan.pairs_per_workgroup), c
+        else:
+            assert plan.units == pairs * plan.query_blocks, c
+            assert plan.query_blocks * plan.wavefronts_per_pair * 32 >= c[2], c     # every query row has a lane
+    assert qf.qflash_plan_unit(plan, -1) == -1 and qf.qflash_plan_unit(plan, plan.workgroups) == -1
+
+
+def test_plan_of_the_benchmark_shapes(lib):
+    """The decompositions the measured figures belong to."""
+    p = qf.qflash_plan_query(None, 64, 12, 197, 64, 64)
+    assert (p.kernel, p.wavefronts_per_pair, p.units, p.tile_by_tile) == (1, 7, 768, 1)
+    p = qf.qflash_plan_query(None, 32, 12, 577, 64, 64)        # two-tile ring, 4 wavefronts: fewer turns per CU
+    assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 4, 5)
+    p = qf.qflash_plan_query(None, 16, 16, 577, 64, 64)        # same turns either way: the larger workgroup
+    assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 7, 3)
+    p = qf.qflash_plan_query(None, 4096, 3, 49, 32, 64, 64, 3)  # four windows per workgroup, bias period 64*3/4
+    assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.bias_period_units) == (1, 4, 2, 48)
+    # XCD x = workgroup % 8 only ever meets an eighth of the bias slices
+    for x in range(8):
+        slices = {(qf.qflash_plan_unit(p, wg) * 4 + s) % 192 for wg in range(x, p.workgroups, 8) for s in range(4)}
+        assert len(slices) == 24, x
+    p = qf.qflash_plan_query(None, 1, 1, 4096, 32, 64)           # too long for LDS at d = 32: streamed
+    assert p.kernel == 0
+    assert lib.qflash_plan_query(None, 1, 1, 64, 64, 64, 0, 0, None) == qf.ERR["NULL"]
+    info = qf.PlanInfo()
+    assert lib.qflash_plan_query(None, 1, 1, 64, 48, 64, 0, 0, ctypes.byref(info)) == qf.ERR["SHAPE"]
+    assert lib.qflash_plan_query(None, 1, 1, 64, 64, 96, 0, 0, ctypes.byref(info)) == qf.ERR["TILE"]
+    assert lib.qflash_plan_query(ctypes.c_void_p(0x1234), 1, 1, 64, 64, 64, 0, 0, ctypes.byref(info)) == qf.ERR["CTX"]
