@@ -121,9 +121,7 @@ int qflash_attention(qflash_ctx* ctx,
  * p points to H entries (host); head h of every batch element uses p[h], and its output has the
  * scale s_V of that head.  All entries must share out_round.  H <= QFLASH_MAX_PARAM_HEADS.
  * bias, if given, is added to the integer score of each head as is, i.e. it has to be expressed
- * in that head's score unit.  Everything else as for qflash_attention; with workgroups that
- * serve several short sequences at once (N <= 64 or so) the weights are always computed
- * arithmetically.
+ * in that head's score unit.  Everything else as for qflash_attention.
  * Errors: as qflash_attention; SHAPE also for H > QFLASH_MAX_PARAM_HEADS, PARAM also for
  * entries that differ in out_round.
  */

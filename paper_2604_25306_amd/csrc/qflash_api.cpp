@@ -191,12 +191,12 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     }
     // Look-up mode: find (or build, once, on this stream) the weight table of each set of
     // constants.  It is used only if every head gets one (the mode is uniform over a launch) and
-    // the largest fits LDS beside K and V.  Workgroups that serve several pairs share one table,
-    // which per-head constants cannot offer.
+    // the largest fits LDS beside K and V.  Workgroups that serve several pairs share one table:
+    // with per-head constants their pairs are therefore one head of consecutive batch elements.
     int rc = 0;
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        bool ok = !hc_dev && ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1);
+        bool ok = !hc_dev && ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1 && !a.same_head);
         int xp[kQflashMaxParamHeads], np_[kQflashMaxParamHeads], max_bytes = 0;
         for (int h = 0; ok && h < n_p; ++h) {
             // weight is 0 at and below -8 octaves: x_p = ceil(8 s_inv / 2^k)

@@ -35,6 +35,7 @@ struct QflashKernelArgs {
     int xcd_period;          // 0, or the number of units after which the bias slices repeat (a multiple of 8)
     int waves_per_head;      // wavefronts that serve one (batch, head) pair inside a workgroup
     int heads_per_wg;        // > 1 only when a pair fits one workgroup (n_qtiles == 1)
+    int same_head;           // heads_per_wg > 1: the pairs of a workgroup are one head of consecutive batch elements
     int resident;            // 1: whole K/V of a head staged in LDS, 0: streamed per KV tile
     int pipelined;           // resident only: K/V tiles are staged one ahead of their use
     int ring;                // pipelined only: LDS holds two KV tiles (in use / being staged), not the whole sequence
@@ -73,7 +74,7 @@ QF_UNIT_HD inline int qflash_unit_of_workgroup(int wg, int units_per_xcd, int xc
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 
 // Choose the kernel variant for BH heads of N rows and fill the work decomposition fields
-// (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd, xcd_period; reads bias, bias_B, H).
+// (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd, xcd_period, same_head; reads bias, bias_B, B, H, per_head).
 // Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
 int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);   // n_cu is the caller's

@@ -595,9 +595,25 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     const int tid = wg_tid - sub * a.waves_per_head * 64;    // thread index within the pair
     const int nthr = a.waves_per_head * 64;
     const int qt = a.heads_per_wg > 1 ? 0 : unit % a.n_qtiles;
-    const int bh = a.heads_per_wg > 1 ? unit * a.heads_per_wg + sub : unit / a.n_qtiles;
-    const bool pair_valid = bh < a.B * a.H;
-    const QflashHeadConsts hc = head_consts(a, pair_valid ? bh : 0);
+    // Several pairs per workgroup: consecutive pairs, or (a.same_head, per-head constants) the same
+    // head of heads_per_wg consecutive batch elements, so that one weight table serves them all.
+    int bh = unit / a.n_qtiles;
+    bool pair_valid = bh < a.B * a.H;
+    if (a.heads_per_wg > 1) {
+        if (a.same_head) {
+            const int b = (unit / a.H) * a.heads_per_wg + sub;
+            bh = b * a.H + unit % a.H;
+            pair_valid = b < a.B;
+        } else {
+            bh = unit * a.heads_per_wg + sub;
+            pair_valid = bh < a.B * a.H;
+        }
+    }
+    // A wavefront whose pair does not exist (the last workgroup of a launch) still helps staging the
+    // weight table, so it must read the constants of the workgroup's head: it stands in for batch
+    // element 0 of that head (pair 0 where all pairs share one set of constants anyway).
+    const int bh_safe = pair_valid ? bh : a.same_head ? unit % a.H : 0;
+    const QflashHeadConsts hc = head_consts(a, bh_safe);
     const int row0 = qt * a.rows_per_wg + (wave - sub * a.waves_per_head) * 32;
     const int i = row0 + li;
 
@@ -605,7 +621,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     int8_t* sK = smem + tbytes + (size_t)sub * ((size_t)k_rows * KROW + (size_t)D * VROW);
     int8_t* sV = sK + (size_t)k_rows * KROW;                // ring: two V^T slots of D x VROW each
 
-    const size_t head_off = (size_t)(pair_valid ? bh : 0) * N * D;
+    const size_t head_off = (size_t)bh_safe * N * D;
     const int8_t* Qh = a.Q + head_off;
     const int8_t* Kh = a.K + head_off;
     const int8_t* Vh = a.V + head_off;
@@ -767,7 +783,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     //      exist in the packed layout and are skipped (the tile code skips them too).
     const int32_t* bias_row = nullptr;
     constexpr bool bias_packed = BIAS == kBiasPacked;
-    if (BIAS) bias_row = bias_lane_base(a, pair_valid ? bh : 0, row0, i, li, g);
+    if (BIAS) bias_row = bias_lane_base(a, bh_safe, row0, i, li, g);
     constexpr bool BPRE_OK = bias_packed && D == 32 && BC == 64;
     v4i bpre[BPRE_OK ? 4 * (BC / 32) : 1];
     if (BPRE_OK) {
@@ -1103,8 +1119,11 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
         a->waves_per_head = kStreamWaves;
     }
     a->n_qtiles = (N + a->rows_per_wg - 1) / a->rows_per_wg;
-    const long long units = a->heads_per_wg > 1 ? ((long long)BH + a->heads_per_wg - 1) / a->heads_per_wg
-                                                : (long long)BH * a->n_qtiles;
+    // per-head constants with several pairs per workgroup: group by head (see the kernel)
+    a->same_head = a->per_head && a->heads_per_wg > 1 ? 1 : 0;
+    const long long units = a->same_head ? (long long)((a->B + a->heads_per_wg - 1) / a->heads_per_wg) * a->H
+                            : a->heads_per_wg > 1 ? ((long long)BH + a->heads_per_wg - 1) / a->heads_per_wg
+                                                  : (long long)BH * a->n_qtiles;
     if (units >= (1ll << 30)) return -1;
     a->n_units = (int)units;
     a->units_per_xcd = (a->n_units + 7) / 8;
@@ -1112,8 +1131,9 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     a->xcd_period = 0;
     if (a->bias) {
         const long long pairs = (long long)a->bias_B * a->H;
-        const long long period = a->heads_per_wg > 1 ? (pairs % a->heads_per_wg == 0 ? pairs / a->heads_per_wg : 0)
-                                                     : pairs * a->n_qtiles;
+        const long long period = a->same_head ? (a->bias_B % a->heads_per_wg == 0 ? pairs / a->heads_per_wg : 0)
+                                 : a->heads_per_wg > 1 ? (pairs % a->heads_per_wg == 0 ? pairs / a->heads_per_wg : 0)
+                                                       : pairs * a->n_qtiles;
         if (period >= 8 && period % 8 == 0 && period <= units) {
             a->xcd_period = (int)period;
             a->units_per_xcd = (int)(((units + period - 1) / period) * (period / 8));

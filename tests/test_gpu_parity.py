@@ -342,14 +342,37 @@ def test_per_head_equal_constants_match_per_tensor_call(gpu):
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("name", ["vit_b16_b64", "deit_b384_b32"])
+@pytest.mark.parametrize("name", ["vit_b16_b64", "deit_b384_b32", "swin_t_s1_b64"])
 def test_per_head_workloads_full_size(gpu, name):
-    """The per-head variant of two benchmark workloads (heads of different range, one scale per
-    head), at full size, every byte."""
+    """The per-head variant of three benchmark workloads (heads of different range, one scale per
+    head; the windowed one with its bias in each head's own score unit, plain and packed), at full
+    size, every byte."""
     wl = make_workload(name, per_head=True)
     H, d = wl.shape[1], wl.shape[3]
     ps = [oracle.derive_params(wl.sQ[h], wl.sK[h], d) for h in range(H)]
-    check_per_head(gpu, wl.Q, wl.K, wl.V, ps, wl.kv_tiles[0], label=wl.name)
+    check_per_head(gpu, wl.Q, wl.K, wl.V, ps, wl.kv_tiles[0], bias=wl.bias, label=wl.name)
+
+
+@pytest.mark.parametrize("shape,bias_bh", [((7, 3, 49, 32), (1, 3)), ((64, 3, 49, 32), (64, 3)), ((130, 6, 20, 32), (16, 6)),
+                                           ((9, 24, 49, 32), (1, 1)), ((5, 2, 64, 64), None), ((33, 4, 30, 64), (3, 4))])
+def test_per_head_several_pairs_per_workgroup(gpu, shape, bias_bh):
+    """Short sequences with per-head constants: a workgroup then takes one head of several
+    consecutive batch elements (so that one weight table serves it); batch sizes that are and are
+    not multiples of the group, bias periods that do and do not fit it."""
+    from workloads import quantize_per_head
+    B, H, N, d = shape
+    rng = np.random.default_rng(B * 1000 + N)
+    gains = np.exp2(rng.uniform(-1.5, 1.5, size=H)).astype(np.float32)
+    Qf = rng.standard_normal(shape).astype(np.float32) * gains[None, :, None, None]
+    Kf = rng.standard_normal(shape).astype(np.float32)
+    Vf = rng.standard_normal(shape).astype(np.float32)
+    (Q, sQ), (K, sK), (V, sV) = (quantize_per_head(x) for x in (Qf, Kf, Vf))
+    ps = [oracle.derive_params(float(sQ[h]), float(sK[h]), d) for h in range(H)]
+    bias = None
+    if bias_bh is not None:
+        bias = rng.integers(-4000, 4000, size=bias_bh + (N, N)).astype(np.int32)
+        bias[rng.random(bias.shape) < 0.1] = EXCLUDED
+    check_per_head(gpu, Q, K, V, ps, 64, bias=bias, label="per-head, several pairs per workgroup")
 
 
 def test_per_head_errors(gpu):

@@ -113,7 +113,10 @@ def swin_window_bias(rng, heads, d, sQ, sK, n_windows=64, win=7):
     excluded = np.zeros((n_windows, heads, n, n), dtype=bool)
     excluded[1::2] = differ[None, None]
     bias_real = np.broadcast_to(rel[None], (n_windows, heads, n, n)).copy()
-    unit = (sQ * sK) / np.sqrt(float(d))
+    # one score unit for the tensor, or one per head (per-head scales: arrays [heads])
+    unit = (np.asarray(sQ, dtype=np.float64) * np.asarray(sK, dtype=np.float64)) / np.sqrt(float(d))
+    if unit.ndim == 1:
+        unit = unit.reshape(1, heads, 1, 1)
     bias_int = np.floor(bias_real / unit + 0.5).astype(np.int64)
     assert np.abs(bias_int).max() < (1 << 20)
     bias = np.where(excluded, np.int64(EXCLUDED), bias_int).astype(np.int32)
@@ -180,14 +183,16 @@ def make_workload(name: str, batch: Optional[int] = None, per_head: bool = False
     seed = 1000 + CONFIG_ORDER.index(name) + 1
     if per_head:
         # per-head variant (Appendix C3): heads get different ranges and their own scales;
-        # sQ, sK, sV are arrays [H].  Not offered for the windowed workloads (their integer bias
-        # is expressed in the score unit of one tensor-wide scale).
-        if windowed:
-            raise ValueError("per-head variant is defined for the non-windowed workloads")
+        # sQ, sK, sV are arrays [H].  The integer bias of a windowed workload is then expressed
+        # head by head in that head's score unit.
         Q, K, V, sQ, sK, sV, rng = make_qkv(shape, seed, dist, sigma, ofrac, per_head=True,
                                             head_gain=head_gains(shape[1]))
-        return Workload(name + "/per_head", Q, K, V, sQ, sK, sV, kv_tiles,
-                        meta={"seed": seed, "dist": dist, "per_head": True})
+        wl = Workload(name + "/per_head", Q, K, V, sQ, sK, sV, kv_tiles,
+                      meta={"seed": seed, "dist": dist, "per_head": True})
+        if windowed:
+            n_windows = 64 if windowed is True else int(windowed)
+            wl.bias, wl.bias_real, wl.excluded = swin_window_bias(rng, shape[1], shape[3], sQ, sK, n_windows=n_windows)
+        return wl
     Q, K, V, sQ, sK, sV, rng = make_qkv(shape, seed, dist, sigma, ofrac)
     wl = Workload(name, Q, K, V, sQ, sK, sV, kv_tiles, meta={"seed": seed, "dist": dist})
     if windowed:
