@@ -185,8 +185,8 @@ int qflash_attention_packed_bias(qflash_ctx* ctx,
  *               nothing.
  *   out_round, kv_tile, hip_stream  as for qflash_attention.  No bias in this entry point (an
  *               integer bias is expressed in a score unit that is only known on the GPU here).
- * The weights are always computed arithmetically (a table would have to be sized by constants
- * the host does not know).
+ * The weight table of the look-up mode, if the constants allow one, is built on the GPU as well
+ * (in the workspace).
  * Errors: CTX, NULL, SHAPE (also: workspace too small), TILE, PARAM (out_round), ALIGN, DEVICE,
  * LAUNCH.
  */

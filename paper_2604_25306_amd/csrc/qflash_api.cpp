@@ -129,7 +129,8 @@ namespace {
 int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
                    const int32_t* bias, int bias_B, int bias_H, int B, int H, int N, int d, int kv_tile,
                    const qflash_params* p, bool per_head, void* hip_stream,
-                   const QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0, bool bias_packed = false) {
+                   QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0, bool bias_packed = false,
+                   uint8_t* dyn_table = nullptr) {
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit, n_cu;
     {
@@ -190,24 +191,42 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         return QFLASH_ERR_DEVICE;
     }
     // Look-up mode: find (or build, once, on this stream) the weight table of each set of
-    // constants.  It is used only if every head gets one (the mode is uniform over a launch) and
-    // the largest fits LDS beside K and V.  Workgroups that serve several pairs share one table:
-    // with per-head constants their pairs are therefore one head of consecutive batch elements.
+    // constants.  A head gets one if it is small enough and the largest of them fits LDS beside K
+    // and V.  If every head has one the whole launch runs in table mode; if only some have (and
+    // the launch carries no bias: the only combination that is built) each workgroup chooses by
+    // its head; otherwise the launch is arithmetic.  Workgroups that serve several pairs share one
+    // table: with per-head constants their pairs are therefore one head of consecutive batch elements.
     int rc = 0;
-    {
+    if (hc_dev) {
+        // Constants made on the GPU: so is the table, by the quantising kernel ahead of this one on
+        // the stream, which also decides whether there is one (mode 3 reads that decision per
+        // workgroup; without mode 3 the table is simply not looked at).
+        bool use_table;
+        {
+            std::lock_guard<std::mutex> lk(g_mu);
+            use_table = ctx->use_table != 0;
+        }
+        if (use_table && dyn_table && a.resident && !bias && qflash_table_fits(a, d, kTableMaxBytes, lds_limit)) {
+            a.exp_mode = 3;
+            a.lut_bytes_max = kTableMaxBytes;
+        }
+    } else {
         std::lock_guard<std::mutex> lk(g_mu);
-        bool ok = !hc_dev && ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1 && !a.same_head);
-        int xp[kQflashMaxParamHeads], np_[kQflashMaxParamHeads], max_bytes = 0;
-        for (int h = 0; ok && h < n_p; ++h) {
+        const bool allowed = ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1 && !a.same_head);
+        int xp[kQflashMaxParamHeads], np_[kQflashMaxParamHeads], max_bytes = 0, n_with = 0;
+        bool has[kQflashMaxParamHeads];
+        for (int h = 0; h < n_p; ++h) {
             // weight is 0 at and below -8 octaves: x_p = ceil(8 s_inv / 2^k)
             const int64_t x_p = (8 * (int64_t)p[h].s_inv + ((int64_t)1 << p[h].x_shift) - 1) >> p[h].x_shift;
             xp[h] = (int)x_p;
             np_[h] = ((int)x_p + 1 + 15) & ~15;
-            if (np_[h] > kTableMaxBytes) ok = false;
-            if (np_[h] > max_bytes) max_bytes = np_[h];
+            has[h] = allowed && x_p + 16 <= kTableMaxBytes;
+            if (has[h] && np_[h] > max_bytes) max_bytes = np_[h];
         }
-        ok = ok && qflash_table_fits(a, d, max_bytes, lds_limit);
-        for (int h = 0; ok && rc == 0 && h < n_p; ++h) {
+        if (max_bytes == 0 || !qflash_table_fits(a, d, max_bytes, lds_limit))
+            for (int h = 0; h < n_p; ++h) has[h] = false;
+        for (int h = 0; rc == 0 && h < n_p; ++h) {
+            if (!has[h]) continue;
             const int32_t key[5] = {p[h].x_shift, p[h].s_inv, p[h].exp_mul, p[h].p_mul, p[h].p_shift};
             int slot = -1;
             for (int i = 0; i < ctx->n_slots; ++i)
@@ -227,14 +246,20 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
                     t.stream = hip_stream; t.n = xp[h] + 1; t.n_padded = np_[h]; t.x_p = xp[h];
                 }
             }
-            if (slot < 0) { ok = false; break; }
+            if (slot < 0) { has[h] = false; continue; }     // no slot left: this head computes
             a.hc[h].lut = ctx->tables + (size_t)slot * kTableMaxBytes;
             a.hc[h].lut_bytes = np_[h];
             a.hc[h].lut_xp = xp[h];
+            ++n_with;
         }
-        if (ok && rc == 0) {
+        if (rc == 0 && n_with == n_p) {
             a.exp_mode = 2;
             a.lut_bytes_max = max_bytes;
+        } else if (rc == 0 && n_with > 0 && !bias) {
+            a.exp_mode = 3;
+            a.lut_bytes_max = max_bytes;
+        } else {
+            for (int h = 0; h < n_p; ++h) { a.hc[h].lut = nullptr; a.hc[h].lut_bytes = 0; a.hc[h].lut_xp = 0; }
         }
     }
     if (rc == 0) rc = qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
@@ -346,16 +371,18 @@ extern "C" int qflash_attention_packed_bias(qflash_ctx* ctx, const int8_t* Q, co
                           n_params == H && H > 1, hip_stream, nullptr, 0, true);
 }
 
-// Workspace layout of the dynamic entry point: [int8 Q | int8 K | int8 V | constants | abs-max scratch]
+// Workspace layout of the dynamic entry point: [int8 Q | int8 K | int8 V | constants | abs-max scratch | weight table]
 namespace {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+size_t dyn_scratch_bytes(size_t n) {     // partial maxima of the abs-max kernel
+    return align256(sizeof(float) * (4 + 3 * (size_t)qflash_dynamic_partials((long long)n)));
+}
 }
 
 extern "C" size_t qflash_dynamic_workspace_bytes(int B, int H, int N, int d) {
     if (B < 1 || H < 1 || N < 1 || d < 1) return 0;
     const size_t n = (size_t)B * H * N * d;
-    return 3 * align256(n) + align256(sizeof(QflashHeadConsts)) +
-           align256(sizeof(float) * (4 + 3 * (size_t)qflash_dynamic_partials((long long)n)));
+    return 3 * align256(n) + align256(sizeof(QflashHeadConsts)) + dyn_scratch_bytes(n) + align256(kTableMaxBytes);
 }
 
 extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const float* Kf, const float* Vf,
@@ -386,6 +413,7 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
     int8_t* Vo = Ko + align256(n);
     QflashHeadConsts* hc_dev = (QflashHeadConsts*)(Vo + align256(n));
     float* scratch = (float*)((int8_t*)hc_dev + align256(sizeof(QflashHeadConsts)));
+    uint8_t* dyn_table = (uint8_t*)scratch + dyn_scratch_bytes(n);    // kTableMaxBytes: a weight table made on the GPU
 
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }
@@ -394,11 +422,11 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
         return QFLASH_ERR_DEVICE;
     }
     int rc = qflash_launch_dynamic_front(Qf, Kf, Vf, Qo, Ko, Vo, (long long)n, std::sqrt((double)d), out_round,
-                                         scratch, hc_dev, info, hip_stream);
+                                         scratch, hc_dev, info, dyn_table, kTableMaxBytes, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
     return attention_impl(ctx, Qo, Ko, Vo, O, nullptr, 0, 0, B, H, N, d, kv_tile, nullptr, false, hip_stream,
-                          hc_dev, out_round);
+                          hc_dev, out_round, false, dyn_table);
 }
 
 extern "C" const char* qflash_strerror(int code) {

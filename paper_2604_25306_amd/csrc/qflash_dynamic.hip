@@ -3,9 +3,10 @@
 //
 //   1. abs-max    max |x| over each of Q, K, V (float32): one partial maximum per workgroup (a
 //                 maximum is exact in any order, so the result does not depend on the grid)
-//   2. quantise   every workgroup finishes the reduction of its tensor; one of them also derives the
+//   2. quantise   every workgroup finishes the reduction of its tensor; one more workgroup derives the
 //                 scales s_X = max|X| / 127 (double) and, from s_Q and s_K, every integer constant of
-//                 the attention kernel -- the same routine the host entry point uses.  Then
+//                 the attention kernel -- the same routine the host entry point uses -- and builds
+//                 the weight table of those constants if it is small enough.  The others compute
 //                 x_hat = clip(rint(x * r), -127, 127), r = float32(127) / max|x|: one float32
 //                 division per tensor, one float32 multiplication and one round-half-to-even per
 //                 element (the precision the rounding decision is defined in)
@@ -19,6 +20,7 @@
 #include "qflash.h"
 #include "qflash_internal.h"
 #include "qflash_derive.h"
+#include "qflash_device.h"
 
 namespace {
 
@@ -81,28 +83,49 @@ __device__ void derive_on_device(const float am[3], double sqrt_d, int out_round
     }
 }
 
-// grid.y = tensor; 4 elements per thread and iteration: 16 B in, 4 B out.  Every workgroup first
-// finishes the abs-max reduction of its tensor from the per-workgroup partial maxima (a few KB,
-// L2-resident); workgroup (0, 0) also does so for the other two tensors and derives the scales and
-// constants for the attention kernel that follows on the stream.
+// grid.y = tensor, grid.x = n_partial streaming workgroups + 1; 4 elements per thread and
+// iteration: 16 B in, 4 B out.  Every streaming workgroup first finishes the abs-max reduction of
+// its tensor from the per-workgroup partial maxima (a few KB, L2-resident).
 __global__ __launch_bounds__(256) void qflash_dyn_quantize(const float* q, const float* k, const float* v,
                                                           int8_t* qo, int8_t* ko, int8_t* vo, long long n4,
                                                           const float* partial, int n_partial, double sqrt_d,
                                                           int out_round, QflashHeadConsts* hc,
-                                                          qflash_dynamic_info* info) {
+                                                          qflash_dynamic_info* info, uint8_t* table, int table_max) {
     __shared__ float wmax[4];
+    __shared__ QflashHeadConsts sh_hc;
+    // One workgroup beyond the streaming ones (x == n_partial, tensor 0) does what needs all three
+    // maxima: it derives the scales and constants for the attention kernel that follows on the
+    // stream and, if there is room for it, builds the weight table of those constants, all while
+    // the others stream.
+    if (blockIdx.x == (unsigned)n_partial) {
+        if (blockIdx.y != 0) return;
+        float a3[3];
+        for (int t = 0; t < 3; ++t) a3[t] = wg_max(partial + t * n_partial, n_partial, wmax);
+        if (threadIdx.x == 0) {
+            derive_on_device(a3, sqrt_d, out_round, &sh_hc, info);
+            // table of x_p + 1 entries, x_p = ceil(8 s_inv / 2^k) (the host's rule), padded to 16
+            const long long x_p = (8ll * sh_hc.s_inv + (1ll << sh_hc.x_shift) - 1) >> sh_hc.x_shift;
+            const long long n_padded = (x_p + 1 + 15) & ~15ll;
+            const bool fits = table != nullptr && n_padded <= (long long)table_max;
+            sh_hc.lut = fits ? table : nullptr;
+            sh_hc.lut_bytes = fits ? (int)n_padded : 0;
+            sh_hc.lut_xp = fits ? (int)x_p : 0;
+            *hc = sh_hc;
+        }
+        __syncthreads();
+        if (sh_hc.lut_bytes > 0) {
+            const QflashHeadConsts h = sh_hc;
+            const ExpConst c = make_exp_const(h);
+            for (int i = threadIdx.x; i < h.lut_bytes; i += 256)
+                table[i] = (uint8_t)(i <= h.lut_xp ? table_entry(i, h.lut_xp, h, c) : 0u);
+        }
+        return;
+    }
     const float* x = blockIdx.y == 0 ? q : blockIdx.y == 1 ? k : v;
     int8_t* y = blockIdx.y == 0 ? qo : blockIdx.y == 1 ? ko : vo;
     const float am = wg_max(partial + blockIdx.y * n_partial, n_partial, wmax);
-    if (blockIdx.x == 0 && blockIdx.y == 0) {
-        float a3[3];
-        a3[0] = am;
-        a3[1] = wg_max(partial + n_partial, n_partial, wmax);
-        a3[2] = wg_max(partial + 2 * n_partial, n_partial, wmax);
-        if (threadIdx.x == 0) derive_on_device(a3, sqrt_d, out_round, hc, info);
-    }
     const float r = am == 0.0f ? 0.0f : __fdiv_rn(127.0f, am);
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)n_partial * blockDim.x) {
         const v4f t = *(const v4f*)(x + 4 * i);
         unsigned w = 0;
 #pragma unroll
@@ -129,13 +152,14 @@ int qflash_dynamic_partials(long long n) {
 
 int qflash_launch_dynamic_front(const float* Qf, const float* Kf, const float* Vf, int8_t* Qo, int8_t* Ko, int8_t* Vo,
                                 long long n, double sqrt_d, int out_round, float* scratch,
-                                QflashHeadConsts* hc_dev, qflash_dynamic_info* info, void* stream) {
+                                QflashHeadConsts* hc_dev, qflash_dynamic_info* info, uint8_t* table, int table_max,
+                                void* stream) {
     hipStream_t st = (hipStream_t)stream;
     const long long n4 = n / 4;
     const int wgs = qflash_dynamic_partials(n);
     float* partial = scratch;         // 3 * wgs words
     hipLaunchKernelGGL(qflash_dyn_absmax, dim3((unsigned)wgs, 3), dim3(256), 0, st, Qf, Kf, Vf, n4, partial);
-    hipLaunchKernelGGL(qflash_dyn_quantize, dim3((unsigned)wgs, 3), dim3(256), 0, st, Qf, Kf, Vf, Qo, Ko, Vo, n4,
-                       (const float*)partial, wgs, sqrt_d, out_round, hc_dev, info);
+    hipLaunchKernelGGL(qflash_dyn_quantize, dim3((unsigned)wgs + 1, 3), dim3(256), 0, st, Qf, Kf, Vf, Qo, Ko, Vo, n4,
+                       (const float*)partial, wgs, sqrt_d, out_round, hc_dev, info, table, table_max);
     return (int)hipGetLastError();
 }

@@ -42,7 +42,8 @@ struct QflashKernelArgs {
     int kv_tile;             // KV tile size the plan was made for
     int n_cu;                // compute units of the device if wave priority alternates by dispatch round, else 0
     // weight mode of the launch (uniform over heads): 2 = every head reads its table,
-    // 1 = arithmetic with x_shift == 0 for every head, 0 = arithmetic
+    // 1 = arithmetic with x_shift == 0 for every head, 0 = arithmetic, 3 = per workgroup: table if the
+    // constants of its head have one (lut_bytes > 0), else arithmetic
     int exp_mode;
     int lut_bytes_max;       // LDS bytes reserved for the table: the largest of all heads
     int per_head;            // 0: hc[0] serves every head; 1: head h uses hc[h] (H <= kQflashMaxParamHeads)
@@ -94,6 +95,10 @@ int qflash_launch_pack_bias(const int32_t* bias, int slices, int N, int32_t* pac
 // each (n a multiple of 4), derivation of the scales and constants into *hc_dev (and *info if not
 // null), quantisation into Qo, Ko, Vo.  scratch: 3 * qflash_dynamic_partials(n) device floats.
 int qflash_dynamic_partials(long long n);
+// table (may be null): room for a weight table of up to table_max bytes; if the table of the
+// derived constants fits, the quantising kernel also builds it (one workgroup more, beside the
+// streaming ones) and records it in *hc_dev (lut, lut_bytes, lut_xp); lut_bytes == 0 says "none".
 int qflash_launch_dynamic_front(const float* Qf, const float* Kf, const float* Vf, int8_t* Qo, int8_t* Ko, int8_t* Vo,
                                 long long n, double sqrt_d, int out_round, float* scratch,
-                                QflashHeadConsts* hc_dev, qflash_dynamic_info* info, void* stream);
+                                QflashHeadConsts* hc_dev, qflash_dynamic_info* info, uint8_t* table, int table_max,
+                                void* stream);

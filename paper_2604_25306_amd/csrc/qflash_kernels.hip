@@ -44,6 +44,7 @@
 #include <stdint.h>
 
 #include "qflash_internal.h"
+#include "qflash_device.h"
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -56,11 +57,6 @@ constexpr int kMInit = -(1 << 21);    // initial running maximum (Algorithm 1)
 
 // ------------------------------------------------------------------ scalar building blocks
 
-// (a * b) >> 32 for operands that fit 24 signed bits: one full-rate v_mul_hi_i32_i24.
-__device__ __forceinline__ int mulhi24(int a, int b) {
-    const int a24 = (a << 8) >> 8, b24 = (b << 8) >> 8;
-    return (int)(((long long)a24 * (long long)b24) >> 32);
-}
 // The two lanes l and l ^ 32 hold the halves of one query row.  One cross-lane swap in the vector
 // ALU (no round trip through the LDS crossbar) hands each of them both values: the swap exchanges
 // the upper half of its first operand with the lower half of the second, so with both operands
@@ -69,44 +65,6 @@ struct HalfPair { int x, y; };
 __device__ __forceinline__ HalfPair both_halves(int v) {
     const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
     return HalfPair{(int)sw[0], (int)sw[1]};
-}
-
-// Loop-invariant constants of Algorithm 2 / Eq. 10 kept in registers.
-struct ExpConst {
-    int k, s_inv, x_floor;   // uniform (scalar registers)
-    int M_v;                 // exp_mul, in a vector register
-    int two_s_inv_v;         // 2 * s_inv, in a vector register
-    int p_mul_hi_v;          // p_mul << (24 - p_shift): the requantised weight lands in byte 3
-};
-
-// Copy a uniform value into a vector register and keep it there: on this chip a two-operand
-// multiply / max / shift with a scalar source issues slower than with two vector sources.
-__device__ __forceinline__ int to_vgpr(int v) {
-    int r;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "s"(v));
-    return r;
-}
-
-// Algorithm 2 for a score t already clamped from below to (m + x_floor).
-//   x' = (t - m) << k,  q = (x' * M) >> 32,  r = x' + q * s_inv,  y = ((r >> 1) + s_inv) >> q.
-// (r >> 1) + s_inv = floor((r + 2 s_inv) / 2) and nested floors of divisions by powers of two
-// compose, so y = (r + 2 s_inv) >> (q + 1).  In the clamped range x' fits 24 bits, 0 <= q <= 28
-// and r + 2 s_inv is positive, so the logical shift is exact.
-// KZ (k == 0): x' = t - m and x' + 2 s_inv = t - (m - 2 s_inv) are two cheap subtractions.
-template <bool KZ>
-__device__ __forceinline__ int shift_exp2(int t, int m, int m2 /* m - 2 s_inv */, const ExpConst& c) {
-    int xs, xs2;
-    if (KZ) {
-        xs = t - m;
-        xs2 = t - m2;
-    } else {
-        const int neg_m = -m;
-        asm("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(xs) : "v"(t), "v"(neg_m), "s"(c.k));
-        xs2 = xs + c.two_s_inv_v;
-    }
-    const int q = mulhi24(xs, c.M_v);
-    const int r2 = __mul24(q, c.s_inv) + xs2;
-    return (int)((unsigned)r2 >> (q + 1));
 }
 
 // Gather byte 3 of four dwords into one dword (v_perm_b32: selector bytes 0-3 pick from the
@@ -200,7 +158,7 @@ struct RowState {
 //   table index = max(0, s - m + x_p) = (s + 2^31) -sat- (m + 2^31 - x_p)
 // is a single unsigned saturating subtraction per score; the maximum is taken unsigned and
 // RowState::m holds m + 2^31.  Algorithm 2 for alpha only sees differences, which are unchanged.
-enum { kExpShift = 0, kExpShift0 = 1, kExpTable = 2 };
+enum { kExpShift = 0, kExpShift0 = 1, kExpTable = 2, kExpAuto = 3 };   // kExpAuto: per workgroup, table if its head has one
 // Bias of a kernel variant: none, the plain [N,N] layout, or the lane-major packed layout.
 enum { kBiasNone = 0, kBiasPlain = 1, kBiasPacked = 2 };
 
@@ -456,14 +414,6 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
         *(v4i*)(dst + 16 * q) = v4i{(int)ev[2 * q], (int)od[2 * q], (int)ev[2 * q + 1], (int)od[2 * q + 1]};
 }
 
-__device__ __forceinline__ ExpConst make_exp_const(const QflashHeadConsts& h) {
-    ExpConst c;
-    c.k = h.x_shift; c.s_inv = h.s_inv; c.x_floor = h.x_floor;
-    c.M_v = to_vgpr(h.exp_mul);
-    c.two_s_inv_v = to_vgpr(2 * h.s_inv);
-    c.p_mul_hi_v = to_vgpr(h.p_mul << (24 - h.p_shift));
-    return c;
-}
 
 // Constants of the head that (batch, head) pair bh belongs to.  bh is uniform over the wavefront,
 // so these are scalar loads from the kernel arguments.
@@ -481,10 +431,17 @@ __device__ __forceinline__ QflashHeadConsts head_consts(const QflashKernelArgs& 
         h.p_shift = __builtin_amdgcn_readfirstlane(g[4]);
         h.a_mul = __builtin_amdgcn_readfirstlane(g[5]);
         h.x_floor = __builtin_amdgcn_readfirstlane(g[6]);
+        // the table, if the GPU built one for these constants (lut_bytes == 0: none)
+        h.lut_xp = __builtin_amdgcn_readfirstlane(g[7]);
+        h.lut_bytes = __builtin_amdgcn_readfirstlane(g[8]);
+        const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane(g[10]), hi = (unsigned)__builtin_amdgcn_readfirstlane(g[11]);
+        h.lut = (const uint8_t*)(((unsigned long long)hi << 32) | lo);
     }
     return h;
 }
-static_assert(offsetof(QflashHeadConsts, x_floor) == 24, "field order read by head_consts");
+static_assert(offsetof(QflashHeadConsts, x_floor) == 24 && offsetof(QflashHeadConsts, lut_xp) == 28 &&
+              offsetof(QflashHeadConsts, lut_bytes) == 32 && offsetof(QflashHeadConsts, lut) == 40,
+              "field order read by head_consts");
 
 // 4x4 byte transpose: rows r[0..3] (byte f = feature f) -> o[f] = (r0.f, r1.f, r2.f, r3.f).
 // v_perm_b32 picks result bytes from the 8 bytes {first operand (4..7), second operand (0..3)}.
@@ -558,7 +515,7 @@ __device__ __forceinline__ const int32_t* bias_lane_base(const QflashKernelArgs&
 }
 
 template <int D, int BC, int BIAS, bool NARROW, int XM>
-__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : (BC == 64 ? 4 : 3)) void qflash_fwd_resident(const QflashKernelArgs a) {
+__device__ __forceinline__ void resident_body(const QflashKernelArgs& a) {
     constexpr int KSTEPS = D / 32;
     constexpr int KROW = D + 16;
     const int N = a.N;
@@ -904,6 +861,24 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 
     else normalise_store<D, 20>(st, Orow, g, a.out_round != 0);
 }
 
+// The kernel: one weight mode for the whole launch, or (kExpAuto: per-head constants of which only
+// some have a table that fits, or constants and table made on the GPU) chosen per workgroup from
+// the constants of its head.  The choice is uniform over the workgroup, so each workgroup runs
+// exactly one of the two bodies.
+template <int D, int BC, int BIAS, bool NARROW, int XM>
+__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : (BC == 64 ? 4 : 3)) void qflash_fwd_resident(const QflashKernelArgs a) {
+    if constexpr (XM == kExpAuto) {
+        const int unit = qflash_unit_of_workgroup(blockIdx.x, a.units_per_xcd, a.xcd_period);
+        if (unit >= a.n_units) return;
+        // any pair of the workgroup: all of them share one head when the constants are per head
+        const int bh = a.heads_per_wg > 1 ? (a.same_head ? unit % a.H : 0) : unit / a.n_qtiles;
+        if (head_consts(a, bh).lut_bytes > 0) resident_body<D, BC, BIAS, NARROW, kExpTable>(a);
+        else resident_body<D, BC, BIAS, NARROW, kExpShift>(a);
+    } else {
+        resident_body<D, BC, BIAS, NARROW, XM>(a);
+    }
+}
+
 // -------------------------------------------------------------------------- stream kernel
 
 constexpr int kStreamWaves = 4;
@@ -997,13 +972,7 @@ __global__ __launch_bounds__(256) void qflash_build_table(uint8_t* tbl, int n, i
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n_padded) return;
     const ExpConst c = make_exp_const(a);
-    unsigned p = 0;
-    if (i < n) {
-        const int x = max(i - x_p, a.x_floor);
-        const int y = shift_exp2<false>(x, 0, -2 * a.s_inv, c);
-        p = ((unsigned)__mul24(y, c.p_mul_hi_v)) >> 24;
-    }
-    tbl[i] = (uint8_t)p;
+    tbl[i] = (uint8_t)(i < n ? table_entry(i, x_p, a, c) : 0u);
 }
 
 template <int D, int BC, int BIAS, bool NARROW, int XM>
@@ -1022,6 +991,11 @@ int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, 
 
 template <int D, int BC, int BIAS, bool NARROW>
 int launch_mode(const QflashKernelArgs& a, size_t lds, int lds_limit, int threads, hipStream_t st) {
+    if (a.exp_mode == kExpAuto) {
+        // only built without a bias (what the per-head and the dynamic entry points need it for)
+        if constexpr (BIAS == kBiasNone) return launch_resident<D, BC, BIAS, NARROW, kExpAuto>(a, lds, lds_limit, threads, st);
+        else return (int)hipErrorInvalidValue;
+    }
     if (a.exp_mode == kExpTable) return launch_resident<D, BC, BIAS, NARROW, kExpTable>(a, lds, lds_limit, threads, st);
     if (a.exp_mode == kExpShift0) return launch_resident<D, BC, BIAS, NARROW, kExpShift0>(a, lds, lds_limit, threads, st);
     return launch_resident<D, BC, BIAS, NARROW, kExpShift>(a, lds, lds_limit, threads, st);
@@ -1195,7 +1169,7 @@ int qflash_launch_fwd(const QflashKernelArgs& a, int d, int kv_tile, int lds_lim
     hipStream_t st = (hipStream_t)stream;
     if (a.ring && (!a.pipelined || d != 64 || a.kv_tile != kv_tile || a.heads_per_wg != 1 || a.waves_per_head < 4))
         return (int)hipErrorInvalidValue;   // the ring is compiled into the tile-by-tile variants only
-    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, a.exp_mode == kExpTable ? a.lut_bytes_max : 0,
+    const size_t lds = a.resident ? resident_lds_bytes(a.N, d, a.heads_per_wg, (a.exp_mode == kExpTable || a.exp_mode == kExpAuto) ? a.lut_bytes_max : 0,
                                                        lds_limit, a.ring ? kv_tile : 0) : 0;
     if (a.resident && lds == 0) return (int)hipErrorInvalidValue;
     const int threads = a.resident ? 64 * a.waves_per_head * a.heads_per_wg : kStreamThreads;
