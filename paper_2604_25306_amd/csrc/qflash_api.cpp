@@ -192,9 +192,8 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     }
     // Look-up mode: find (or build, once, on this stream) the weight table of each set of
     // constants.  A head gets one if it is small enough and the largest of them fits LDS beside K
-    // and V.  If every head has one the whole launch runs in table mode; if only some have (and
-    // the launch carries no bias: the only combination that is built) each workgroup chooses by
-    // its head; otherwise the launch is arithmetic.  Workgroups that serve several pairs share one
+    // and V.  If every head has one the whole launch runs in table mode; if only some have, each
+    // workgroup chooses by its head; otherwise the launch is arithmetic.  Workgroups that serve several pairs share one
     // table: with per-head constants their pairs are therefore one head of consecutive batch elements.
     int rc = 0;
     if (hc_dev) {
@@ -255,7 +254,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         if (rc == 0 && n_with == n_p) {
             a.exp_mode = 2;
             a.lut_bytes_max = max_bytes;
-        } else if (rc == 0 && n_with > 0 && !bias) {
+        } else if (rc == 0 && n_with > 0) {
             a.exp_mode = 3;
             a.lut_bytes_max = max_bytes;
         } else {

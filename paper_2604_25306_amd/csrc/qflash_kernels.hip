@@ -991,11 +991,7 @@ int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, 
 
 template <int D, int BC, int BIAS, bool NARROW>
 int launch_mode(const QflashKernelArgs& a, size_t lds, int lds_limit, int threads, hipStream_t st) {
-    if (a.exp_mode == kExpAuto) {
-        // only built without a bias (what the per-head and the dynamic entry points need it for)
-        if constexpr (BIAS == kBiasNone) return launch_resident<D, BC, BIAS, NARROW, kExpAuto>(a, lds, lds_limit, threads, st);
-        else return (int)hipErrorInvalidValue;
-    }
+    if (a.exp_mode == kExpAuto) return launch_resident<D, BC, BIAS, NARROW, kExpAuto>(a, lds, lds_limit, threads, st);
     if (a.exp_mode == kExpTable) return launch_resident<D, BC, BIAS, NARROW, kExpTable>(a, lds, lds_limit, threads, st);
     if (a.exp_mode == kExpShift0) return launch_resident<D, BC, BIAS, NARROW, kExpShift0>(a, lds, lds_limit, threads, st);
     return launch_resident<D, BC, BIAS, NARROW, kExpShift>(a, lds, lds_limit, threads, st);
