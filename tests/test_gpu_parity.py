@@ -295,6 +295,29 @@ def test_two_tile_ring(gpu, shape, with_bias, tile):
     check(gpu, Q, K, V, p, tile, bias=bias, label="ring")
 
 
+@pytest.mark.parametrize("tile", [64, 128])
+def test_streamed_kernel_with_bias(gpu, tile):
+    """d = 32 and a sequence too long for LDS: the kernel that streams KV tiles, with a bias in both
+    layouts, exclusions across whole tiles and a ragged last tile."""
+    shape = (1, 2, 2100, 32)
+    assert paper_plan(shape, tile).kernel == 0
+    Q, K, V, sQ, sK, _ = rand_case(shape, 2100 + tile)
+    p = oracle.derive_params(sQ, sK, 32)
+    rng = np.random.default_rng(tile)
+    bias = rng.integers(-3000, 3000, size=(1, 2, 2100, 2100)).astype(np.int32)
+    bias[rng.random(bias.shape) < 0.05] = EXCLUDED
+    bias[0, 0, 17, :1024] = EXCLUDED
+    bias[0, 1, 18, :] = EXCLUDED
+    check(gpu, Q, K, V, p, tile, bias=bias, label="streamed + bias")
+    ps = [p, oracle.derive_params(sQ * 1.7, sK, 32)]
+    check_per_head(gpu, Q, K, V, ps, tile, bias=bias, label="streamed + bias, per head")
+
+
+def paper_plan(shape, tile, bias_bh=(0, 0)):
+    import paper_2604_25306_amd as qf
+    return qf.qflash_plan_query(None, shape[0], shape[1], shape[2], shape[3], tile, *bias_bh)
+
+
 # ------------------------------------------------------------- per-head constants (Appendix C3)
 
 
