@@ -861,12 +861,25 @@ __device__ __forceinline__ void resident_body(const QflashKernelArgs& a) {
     else normalise_store<D, 20>(st, Orow, g, a.out_round != 0);
 }
 
+// Wavefronts per SIMD the register allocation has to allow.  Short sequences (NARROW): 4, and 6
+// for d = 32 with kv_tile 64 (windowed attention: 80 registers, three workgroups of eight
+// wavefronts per compute unit) -- except that its variants that hold the 32 prefetched words of a
+// packed bias and compute weights arithmetically spill at 80 registers and run a fifth faster at
+// 96 (5 per SIMD).  Long sequences: 4 with kv_tile 64 (the two-tile ring counts on four slots),
+// 3 with kv_tile 128.
+template <int D, int BC, int BIAS, bool NARROW, int XM>
+constexpr int resident_min_waves() {
+    if (!NARROW) return BC == 64 ? 4 : 3;
+    if (D == 32 && BC == 64) return (BIAS == kBiasPacked && XM != kExpTable) ? 5 : 6;
+    return 4;
+}
+
 // The kernel: one weight mode for the whole launch, or (kExpAuto: per-head constants of which only
 // some have a table that fits, or constants and table made on the GPU) chosen per workgroup from
 // the constants of its head.  The choice is uniform over the workgroup, so each workgroup runs
 // exactly one of the two bodies.
 template <int D, int BC, int BIAS, bool NARROW, int XM>
-__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), NARROW ? ((D == 32 && BC == 64) ? 6 : 4) : (BC == 64 ? 4 : 3)) void qflash_fwd_resident(const QflashKernelArgs a) {
+__global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), (resident_min_waves<D, BC, BIAS, NARROW, XM>())) void qflash_fwd_resident(const QflashKernelArgs a) {
     if constexpr (XM == kExpAuto) {
         const int unit = qflash_unit_of_workgroup(blockIdx.x, a.units_per_xcd, a.xcd_period);
         if (unit >= a.n_units) return;
