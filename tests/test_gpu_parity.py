@@ -502,7 +502,7 @@ def test_dynamic_headline_shape_full_size(gpu):
 # ------------------------------------------------------------------- seeded random sweep
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(40))
 def test_random_configurations(gpu, seed):
     """Shapes, tile size, scales, bias, exclusion, rounding mode and scale granularity drawn from a
     seed: every kernel family and staging mode meets combinations no hand-written case lists."""
@@ -510,7 +510,7 @@ def test_random_configurations(gpu, seed):
     rng = np.random.default_rng(70000 + seed)
     d = int(rng.choice([32, 64]))
     tile = int(rng.choice([64, 128]))
-    N = int(rng.choice([rng.integers(1, 65), rng.integers(65, 257), rng.integers(257, 700)]))
+    N = int(rng.choice([rng.integers(1, 65), rng.integers(65, 257), rng.integers(257, 700), rng.integers(700, 1400)]))
     B, H = int(rng.integers(1, 4)), int(rng.integers(1, 6))
     shape = (B, H, N, d)
     per_head = bool(rng.integers(0, 3) == 0)
