@@ -30,6 +30,7 @@ extern "C" {
 #define QFLASH_ERR_LAUNCH  (-6)  /* the kernel launch was rejected by the runtime                 */
 #define QFLASH_ERR_CTX     (-7)  /* the context is not a live context of this library             */
 #define QFLASH_ERR_ALIGN   (-8)  /* Q, K, V or O is not 16-byte aligned, bias not 4-byte aligned  */
+#define QFLASH_ERR_SCRATCH (-9)  /* qflash_attention_static: table larger than its static memory  */
 
 #define QFLASH_MAX_N       4096  /* 128*127*N must stay below 2^31 with margin                    */
 #define QFLASH_MAX_PARAM_HEADS 64 /* most heads qflash_attention_per_head accepts                 */
@@ -114,6 +115,29 @@ int qflash_attention(qflash_ctx* ctx,
                      const int32_t* bias, int bias_B, int bias_H,
                      int B, int H, int N, int d, int kv_tile,
                      const qflash_params* p, void* hip_stream);
+
+/*
+ * qflash_attention for callers that must not allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result bits.  The
+ * only device memory the library needs beyond inputs and outputs, the weight table of the look-up
+ * mode (see qflash_configure), lives here in a static device array of QFLASH_STATIC_TABLE_BYTES
+ * that each GPU holds from the moment the library is loaded until the process ends; its address is
+ * looked up once per context in qflash_create.  Every call rebuilds the table there (one small
+ * kernel ahead of the attention kernel on hip_stream), so nothing is cached, nothing is allocated
+ * or freed, and the context's table cache is not touched.
+ *   - Constants whose table (about 8 * s_inv / 2^x_shift bytes) does not fit the array are
+ *     refused with QFLASH_ERR_SCRATCH; with QFLASH_CFG_EXP_TABLE set to 0 the call computes
+ *     arithmetically, uses no such memory and accepts every constant qflash_attention accepts.
+ *   - All calls on one GPU share the one array: calls on different streams (or from different
+ *     contexts of the same GPU) that overlap in time race on it.  Calls on one stream are safe.
+ * Errors: as qflash_attention, plus SCRATCH; DEVICE also if the array's address was not available.
+ */
+#define QFLASH_STATIC_TABLE_BYTES (32 * 1024)
+int qflash_attention_static(qflash_ctx* ctx,
+                            const int8_t* Q, const int8_t* K, const int8_t* V, int8_t* O,
+                            const int32_t* bias, int bias_B, int bias_H,
+                            int B, int H, int N, int d, int kv_tile,
+                            const qflash_params* p, void* hip_stream);
 
 /*
  * The same pass with per-head quantisation (Section 3.2 and Appendix C3: per-tensor and per-head

@@ -7,6 +7,7 @@ CPU or PyTorch fallback; if the library has not been built, importing ``binding`
 from .binding import (  # noqa: F401
     QFlashError, QFlashParams, Context, library_path, load_library,
     qflash_params_from_scales, qflash_create, qflash_configure, qflash_attention,
+    qflash_attention_static,
     qflash_attention_per_head, qflash_dynamic_workspace_bytes, qflash_attention_dynamic, DynamicInfo,
     qflash_destroy, qflash_strerror, EXCLUDED, ERR, CFG_EXP_TABLE,
     MAX_PARAM_HEADS, qflash_packed_bias_bytes, qflash_pack_bias, qflash_attention_packed_bias,

@@ -12,9 +12,10 @@ _lib = None
 EXCLUDED = -(1 << 31)
 
 ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, "LAUNCH": -6,
-       "CTX": -7, "ALIGN": -8}
+       "CTX": -7, "ALIGN": -8, "SCRATCH": -9}
 
 EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
+           "qflash_attention_static",
            "qflash_attention_per_head", "qflash_dynamic_workspace_bytes", "qflash_attention_dynamic",
            "qflash_packed_bias_bytes", "qflash_pack_bias", "qflash_attention_packed_bias",
            "qflash_plan_query", "qflash_plan_unit",
@@ -84,6 +85,8 @@ def load_library():
                                                  ctypes.c_size_t, vp]
         lib.qflash_attention_per_head.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
         lib.qflash_attention.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, pp, vp]
+        lib.qflash_attention_static.restype = ci
+        lib.qflash_attention_static.argtypes = lib.qflash_attention.argtypes
         lib.qflash_packed_bias_bytes.restype = ctypes.c_size_t
         lib.qflash_packed_bias_bytes.argtypes = [ci, ci, ci]
         lib.qflash_pack_bias.restype = ci
@@ -171,6 +174,16 @@ def qflash_attention(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, b
     rc = load_library().qflash_attention(ctypes.c_void_p(ctx), *args, int(kv_tile), ctypes.byref(params), st)
     if rc != 0:
         raise QFlashError(rc, "qflash_attention")
+
+
+def qflash_attention_static(ctx: int, Q, K, V, O, params: QFlashParams, kv_tile: int, bias=None,
+                            stream: Optional[int] = None) -> None:
+    """``qflash_attention`` through the entry point that allocates no device memory."""
+    args, st = _marshal(Q, K, V, O, bias, stream)
+    rc = load_library().qflash_attention_static(ctypes.c_void_p(ctx), *args, int(kv_tile),
+                                                ctypes.byref(params), st)
+    if rc != 0:
+        raise QFlashError(rc, "qflash_attention_static")
 
 
 def params_array(params):
@@ -300,6 +313,9 @@ class Context:
             qflash_attention(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
         else:
             qflash_attention_per_head(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
+
+    def attention_static(self, Q, K, V, O, params, kv_tile, bias=None, stream=None):
+        qflash_attention_static(self.handle, Q, K, V, O, params, kv_tile, bias, stream)
 
     def pack_bias(self, bias, stream=None):
         """Returns the packed copy of ``bias`` (a new int32 CUDA tensor) for ``attention_packed_bias``."""

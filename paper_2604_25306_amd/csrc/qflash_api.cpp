@@ -26,12 +26,21 @@ struct TableSlot {
 constexpr int kTableSlots = 32;
 constexpr int kTableMaxBytes = 40 * 1024;
 
+// Device memory of the entry point that allocates nothing (qflash_attention_static): room for one
+// weight table.  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code this name is only a stand-in for the symbol: the address that kernels and copies may use is
+// the one hipGetSymbolAddress reports for the current device (qflash_create, kept in the context).
+constexpr int kScratchBytes = QFLASH_STATIC_TABLE_BYTES;
+static_assert(kScratchBytes % 256 == 0 && kScratchBytes <= kTableMaxBytes, "one table at most");
+static __device__ __align__(256) uint8_t scratch[kScratchBytes];
+
 struct qflash_ctx {
     int device;
     int lds_limit;        // LDS bytes one workgroup may allocate on this device
     int n_cu;             // compute units
     int use_table;        // QFLASH_CFG_EXP_TABLE
     uint8_t* tables;      // device, kTableSlots x kTableMaxBytes
+    uint8_t* scratch_ptr; // device address of `scratch` on this context's GPU, or nullptr
     int n_slots;          // slots in use
     TableSlot slots[kTableSlots];
 };
@@ -88,6 +97,13 @@ extern "C" int qflash_create(qflash_ctx** out, int device_id) {
         (void)hipGetLastError();
         c->tables = nullptr;   // the arithmetic mode needs no tables
     }
+    // Address of this device's copy of the static table memory (the context's device is current).
+    c->scratch_ptr = nullptr;
+    {
+        void* sp = nullptr;
+        if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) == hipSuccess) c->scratch_ptr = (uint8_t*)sp;
+        else (void)hipGetLastError();
+    }
     if (switched) (void)hipSetDevice(cur);
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -130,15 +146,19 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
                    const int32_t* bias, int bias_B, int bias_H, int B, int H, int N, int d, int kv_tile,
                    const qflash_params* p, bool per_head, void* hip_stream,
                    QflashHeadConsts* hc_dev = nullptr, int out_round_dev = 0, bool bias_packed = false,
-                   uint8_t* dyn_table = nullptr) {
+                   uint8_t* dyn_table = nullptr, bool static_table = false) {
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit, n_cu;
+    uint8_t* scratch_ptr;
+    bool table_wanted;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
         device = ctx->device;
         lds_limit = ctx->lds_limit;
         n_cu = ctx->n_cu;
+        scratch_ptr = ctx->scratch_ptr;
+        table_wanted = ctx->use_table != 0;
     }
     if (!Q || !K || !V || !O || (!p && !hc_dev)) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
@@ -160,6 +180,16 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     }
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
     if (bias && ((uintptr_t)bias & (bias_packed ? 15u : 3u))) return QFLASH_ERR_ALIGN;
+    // The entry point that allocates nothing keeps its one weight table in the static device array:
+    // constants whose table is larger than that are refused, not silently run another way.
+    int static_xp = 0, static_np = 0;
+    if (static_table && table_wanted) {
+        const int64_t x_p = (8 * (int64_t)p[0].s_inv + ((int64_t)1 << p[0].x_shift) - 1) >> p[0].x_shift;
+        if (x_p + 16 > kScratchBytes) return QFLASH_ERR_SCRATCH;
+        if (!scratch_ptr) return QFLASH_ERR_DEVICE;
+        static_xp = (int)x_p;
+        static_np = ((int)x_p + 1 + 15) & ~15;
+    }
 
     static_assert(QFLASH_MAX_PARAM_HEADS == kQflashMaxParamHeads, "header and kernel arguments disagree");
     QflashKernelArgs a;
@@ -208,6 +238,18 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         if (use_table && dyn_table && a.resident && !bias && qflash_table_fits(a, d, kTableMaxBytes, lds_limit)) {
             a.exp_mode = 3;
             a.lut_bytes_max = kTableMaxBytes;
+        }
+    } else if (static_table) {
+        // One table, rebuilt by every call in the static device array ahead of the attention kernel
+        // on the same stream (the array keeps the last call's table and every byte the kernel
+        // stages, [0, static_np), is rewritten).  No lock: nothing of the context is touched.
+        if (static_np > 0 && a.resident && qflash_table_fits(a, d, static_np, lds_limit)) {
+            rc = qflash_launch_build_table(scratch_ptr, static_xp + 1, static_np, static_xp, a.hc[0], hip_stream);
+            a.hc[0].lut = scratch_ptr;
+            a.hc[0].lut_bytes = static_np;
+            a.hc[0].lut_xp = static_xp;
+            a.exp_mode = 2;
+            a.lut_bytes_max = static_np;
         }
     } else {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -273,6 +315,13 @@ extern "C" int qflash_attention(qflash_ctx* ctx, const int8_t* Q, const int8_t* 
                                 int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B, int H,
                                 int N, int d, int kv_tile, const qflash_params* p, void* hip_stream) {
     return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, false, hip_stream);
+}
+
+extern "C" int qflash_attention_static(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
+                                       int8_t* O, const int32_t* bias, int bias_B, int bias_H, int B, int H,
+                                       int N, int d, int kv_tile, const qflash_params* p, void* hip_stream) {
+    return attention_impl(ctx, Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, false, hip_stream,
+                          nullptr, 0, false, nullptr, true);
 }
 
 extern "C" int qflash_attention_per_head(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8_t* V,
@@ -439,6 +488,7 @@ extern "C" const char* qflash_strerror(int code) {
         case QFLASH_ERR_LAUNCH: return "kernel launch failed";
         case QFLASH_ERR_CTX: return "not a live qflash context";
         case QFLASH_ERR_ALIGN: return "Q, K, V, O must be 16-byte aligned and bias 4-byte aligned";
+        case QFLASH_ERR_SCRATCH: return "the weight table of these constants exceeds the static device memory of qflash_attention_static";
         default: return "unknown qflash error code";
     }
 }
