@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--plain-bias", action="store_true",
                     help="workloads with a bias: hand it over in the plain [N,N] layout on every call "
                          "instead of packing it once before the timed region (qflash_pack_bias)")
+    ap.add_argument("--no-table", action="store_true",
+                    help="evaluate the weight of every score arithmetically (Algorithm 2 in the vector ALUs) "
+                         "instead of reading it from the table in LDS; same bits")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device-to-device copy, so that a rocprofv3 --pmc "
                          "trace of this command holds a kernel of known HBM traffic")
@@ -99,6 +102,8 @@ def main():
         sets.append((q, k, v, torch.empty(q.shape, dtype=torch.int8, device=dev)))
     bias = torch.from_numpy(wl.bias).to(dev) if wl.bias is not None else None
     ctx = qf.Context(0)
+    if args.no_table:
+        ctx.configure(qf.CFG_EXP_TABLE, 0)
     # The bias of a windowed layer is a constant of the layer: packed once, outside the timed region.
     packed = ctx.pack_bias(bias) if bias is not None and not args.plain_bias else None
     if packed is not None:

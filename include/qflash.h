@@ -239,7 +239,13 @@ int qflash_attention_dynamic(qflash_ctx* ctx,
  *
  *   bias_B, bias_H   extents of the bias the call would be given, or 0, 0 for none.
  *   kernel           0: KV tiles streamed through LDS, 128 query rows per workgroup;
- *                    1: K and V of a (batch, head) pair resident in LDS; 2: two KV tiles in LDS.
+ *                    1: K and V of a (batch, head) pair resident in LDS; 2: two KV tiles in LDS;
+ *                    3: one workgroup per compute unit holds Q, K, V of several pairs in LDS (short
+ *                    sequences, d = 64, kv_tile 64, no bias, one set of constants, few enough pairs for
+ *                    a single round of workgroups; assumes a weight table of 32 KiB).  For kernel 3:
+ *                    wavefronts_per_pair is the number of wavefronts of a workgroup, query_blocks the
+ *                    32-row blocks of a pair, units = workgroups, and workgroup w takes pairs
+ *                    [w * pairs_per_workgroup, (w + 1) * pairs_per_workgroup).
  *   pairs_per_workgroup, wavefronts_per_pair, query_blocks (workgroups a pair is split over),
  *   units (pieces of work = workgroups that have rows), workgroups (launched; a few may be idle),
  *   tile_by_tile (1: KV tiles staged one ahead of their use), bias_period_units (0, or the number of

@@ -23,6 +23,7 @@ struct TableSlot {
     int n, n_padded, x_p;
 };
 
+constexpr int kPlanQueryTableBytes = 32 * 1024;   // table size qflash_plan_query assumes (it is not given constants)
 constexpr int kTableSlots = 32;
 constexpr int kTableMaxBytes = 40 * 1024;
 
@@ -137,7 +138,18 @@ extern "C" int qflash_configure(qflash_ctx* ctx, int key, int value) {
     return QFLASH_OK;
 }
 
+#ifdef QF_TRACE
+static unsigned long long* g_trace = nullptr;
+extern "C" void qflash_debug_trace(void* buf) { g_trace = (unsigned long long*)buf; }
+#endif
+
 namespace {
+
+// Whether the planned launch can hold a weight table of table_bytes in LDS and copying it pays.
+bool table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds_limit) {
+    if (a.cu_mode) return table_bytes <= a.cu_table_lds && 4ll * a.cu_heads * a.N * d >= (long long)table_bytes;
+    return qflash_table_fits(a, d, table_bytes, lds_limit) != 0;
+}
 
 // Shared by the per-tensor and the per-head entry points: n_p = 1 (p[0] serves every head) or H.
 // hc_dev != nullptr: the constants are computed on the GPU (dynamic quantisation); p is then not
@@ -203,6 +215,9 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.per_head = per_head ? 1 : 0;
     a.hc_dev = hc_dev;
     a.n_cu = n_cu;
+#ifdef QF_TRACE
+    a.trace = g_trace;
+#endif
     bool all_k0 = hc_dev == nullptr;
     for (int h = 0; h < n_p; ++h) {
         if (!qflash_fill_head_consts(p[h], &a.hc[h])) return QFLASH_ERR_PARAM;
@@ -211,6 +226,22 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.exp_mode = all_k0 ? 1 : 0;
     a.lut_bytes_max = 0;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
+    // The kernel that gives a whole compute unit to one workgroup, where the shape allows it: its LDS
+    // budget depends on the size of the weight table the call would use.
+    {
+        int table_hint = 0;
+        if (hc_dev) {
+            table_hint = (table_wanted && dyn_table) ? kTableMaxBytes : 0;
+        } else if (static_table) {
+            table_hint = static_np;
+        } else if (table_wanted && !per_head) {
+            const int64_t x_p = (8 * (int64_t)p[0].s_inv + ((int64_t)1 << p[0].x_shift) - 1) >> p[0].x_shift;
+            if (x_p + 16 <= kTableMaxBytes) table_hint = ((int)x_p + 1 + 15) & ~15;
+        }
+        // a table only pays while it is smaller than the Q, K, V, O bytes of the workgroup
+        if (!qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, table_hint, &a) && table_hint > 0)
+            qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, 0, &a);
+    }
     // wave priority by dispatch round: only for launches of two to four rounds (0 = off)
     if (a.n_units <= n_cu || a.n_units > 4 * n_cu) a.n_cu = 0;
 
@@ -235,7 +266,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
             std::lock_guard<std::mutex> lk(g_mu);
             use_table = ctx->use_table != 0;
         }
-        if (use_table && dyn_table && a.resident && !bias && qflash_table_fits(a, d, kTableMaxBytes, lds_limit)) {
+        if (use_table && dyn_table && a.resident && !bias && table_fits(a, d, kTableMaxBytes, lds_limit)) {
             a.exp_mode = 3;
             a.lut_bytes_max = kTableMaxBytes;
         }
@@ -243,7 +274,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         // One table, rebuilt by every call in the static device array ahead of the attention kernel
         // on the same stream (the array keeps the last call's table and every byte the kernel
         // stages, [0, static_np), is rewritten).  No lock: nothing of the context is touched.
-        if (static_np > 0 && a.resident && qflash_table_fits(a, d, static_np, lds_limit)) {
+        if (static_np > 0 && a.resident && table_fits(a, d, static_np, lds_limit)) {
             rc = qflash_launch_build_table(scratch_ptr, static_xp + 1, static_np, static_xp, a.hc[0], hip_stream);
             a.hc[0].lut = scratch_ptr;
             a.hc[0].lut_bytes = static_np;
@@ -264,7 +295,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
             has[h] = allowed && x_p + 16 <= kTableMaxBytes;
             if (has[h] && np_[h] > max_bytes) max_bytes = np_[h];
         }
-        if (max_bytes == 0 || !qflash_table_fits(a, d, max_bytes, lds_limit))
+        if (max_bytes == 0 || !table_fits(a, d, max_bytes, lds_limit))
             for (int h = 0; h < n_p; ++h) has[h] = false;
         for (int h = 0; rc == 0 && h < n_p; ++h) {
             if (!has[h]) continue;
@@ -303,7 +334,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
             for (int h = 0; h < n_p; ++h) { a.hc[h].lut = nullptr; a.hc[h].lut_bytes = 0; a.hc[h].lut_xp = 0; }
         }
     }
-    if (rc == 0) rc = qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+    if (rc == 0) rc = a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream) : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
     return QFLASH_OK;
@@ -357,6 +388,15 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
     a.n_cu = n_cu;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
     std::memset(out, 0, sizeof *out);
+    if (qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, kPlanQueryTableBytes, &a)) {
+        out->kernel = 3;
+        out->pairs_per_workgroup = a.cu_heads;
+        out->wavefronts_per_pair = a.cu_waves;
+        out->query_blocks = (N + 31) / 32;
+        out->units = a.cu_groups;
+        out->workgroups = a.cu_groups;
+        return QFLASH_OK;
+    }
     out->kernel = !a.resident ? 0 : a.ring ? 2 : 1;
     out->pairs_per_workgroup = a.heads_per_wg;
     out->wavefronts_per_pair = a.waves_per_head;
@@ -371,6 +411,7 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
 
 extern "C" int qflash_plan_unit(const qflash_plan_info* plan, int workgroup) {
     if (!plan || workgroup < 0 || workgroup >= plan->workgroups) return -1;
+    if (plan->kernel == 3) return workgroup;
     const int unit = qflash_unit_of_workgroup(workgroup, plan->units_per_xcd, plan->bias_period_units);
     return unit < plan->units ? unit : -1;
 }

@@ -46,6 +46,15 @@ struct QflashKernelArgs {
     // constants of its head have one (lut_bytes > 0), else arithmetic
     int exp_mode;
     int lut_bytes_max;       // LDS bytes reserved for the table: the largest of all heads
+    // whole-compute-unit kernel (qflash_plan_cu): 1 if the launch takes it
+    int cu_mode;
+    int cu_heads;            // (batch, head) pairs per workgroup
+    int cu_groups;           // workgroups
+    int cu_waves;            // wavefronts per workgroup (at most 16)
+    int cu_table_lds;        // LDS bytes reserved for the weight table (a multiple of 1 KiB)
+#ifdef QF_TRACE
+    unsigned long long* trace;   // instrumented builds only: [workgroup][wavefront][16] timestamps
+#endif
     int per_head;            // 0: hc[0] serves every head; 1: head h uses hc[h] (H <= kQflashMaxParamHeads)
     // Constants computed on the GPU (dynamic quantisation): if set, the kernel reads this device
     // structure instead of hc[]; exp_mode is then 0 (the host does not know the constants).
@@ -79,6 +88,15 @@ int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_
 // Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
 int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);   // n_cu is the caller's
+
+// The kernel that gives a whole compute unit to one workgroup (short sequences, 64 features, tile 64,
+// no bias, one set of constants): decides whether the launch takes it, assuming a weight table of
+// table_bytes (0: none), and fills the cu_* fields.  Reads bias, per_head, n_cu (0: 256).  Returns cu_mode.
+int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_bytes, QflashKernelArgs* args);
+int qflash_launch_fwd_cu(const QflashKernelArgs& args, int lds_limit, void* stream);
+
+// GPUs per process for which per-device launch set-up is remembered.
+constexpr int kQflashMaxDevices = 64;
 
 // 1 if the resident kernel can also hold a weight table of table_bytes in LDS and copying it pays.
 int qflash_table_fits(const QflashKernelArgs& args, int d, int table_bytes, int lds_limit);

@@ -130,6 +130,12 @@ def test_plan_covers_every_unit_exactly_once(lib):
         plan = qf.qflash_plan_query(None, *c)
         taken = [u for u in _units_taken(plan) if u >= 0]
         assert sorted(taken) == list(range(plan.units)), c
+        pairs = c[0] * c[1]
+        if plan.kernel == 3:        # one workgroup per compute unit, several whole pairs each
+            assert plan.units == plan.workgroups == -(-pairs // plan.pairs_per_workgroup) <= 256, c
+            assert c[3] == 64 and c[4] == 64 and c[2] <= 256 and c[5] == 0, c
+            assert 1 <= plan.wavefronts_per_pair <= 16 and plan.query_blocks * 32 >= c[2], c
+            continue
         assert plan.workgroups % 8 == 0 and plan.workgroups >= plan.units, c
         assert plan.bias_period_units % 8 == 0, c
         pairs = c[0] * c[1]
@@ -143,8 +149,10 @@ def test_plan_covers_every_unit_exactly_once(lib):
 
 def test_plan_of_the_benchmark_shapes(lib):
     """The decompositions the measured figures belong to."""
-    p = qf.qflash_plan_query(None, 64, 12, 197, 64, 64)
-    assert (p.kernel, p.wavefronts_per_pair, p.units, p.tile_by_tile) == (1, 7, 768, 1)
+    p = qf.qflash_plan_query(None, 64, 12, 197, 64, 64)       # three pairs per compute unit, 16 wavefronts
+    assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.units, p.query_blocks) == (3, 3, 16, 256, 7)
+    p = qf.qflash_plan_query(None, 1024, 6, 197, 64, 64)     # too many pairs for one round: a workgroup per pair
+    assert (p.kernel, p.wavefronts_per_pair, p.units, p.tile_by_tile) == (1, 7, 6144, 1)
     p = qf.qflash_plan_query(None, 32, 12, 577, 64, 64)        # two-tile ring, 4 wavefronts: fewer turns per CU
     assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 4, 5)
     p = qf.qflash_plan_query(None, 16, 16, 577, 64, 64)        # same turns either way: the larger workgroup

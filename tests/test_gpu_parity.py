@@ -295,6 +295,36 @@ def test_two_tile_ring(gpu, shape, with_bias, tile):
     check(gpu, Q, K, V, p, tile, bias=bias, label="ring")
 
 
+# (batch, heads, N): several pairs per workgroup, a last workgroup with fewer pairs than the others,
+# every number of 8-key groups in the ragged tile, single tiles, a sequence of a single row, sequences
+# that end exactly on a 16-row block and on a tile, four pairs per workgroup
+WHOLE_CU_SHAPES = [(103, 5, 197), (86, 3, 70), (64, 5, 1), (300, 1, 16), (301, 1, 17), (70, 4, 64), (50, 6, 65),
+                   (257, 1, 128), (43, 6, 129), (90, 3, 200), (33, 8, 208), (40, 7, 224), (37, 7, 225), (32, 9, 249),
+                   (100, 3, 256), (1, 3, 197), (8, 6, 197), (128, 8, 33), (51, 5, 73), (51, 5, 81), (51, 5, 89),
+                   (51, 5, 97), (51, 5, 105), (51, 5, 113), (51, 5, 121),
+                   # four pairs per workgroup fit only without the weight table: arithmetic weights, and the
+                   # fourth pair has no wavefronts of its own at the start (its loads ride with the third's)
+                   (84, 12, 197)]
+
+
+@pytest.mark.parametrize("bhn", WHOLE_CU_SHAPES)
+def test_whole_compute_unit_kernel(gpu, bhn):
+    """Short sequences with 64 features, tile 64 and no bias, few enough pairs for one round of
+    workgroups: the kernel in which one workgroup per compute unit holds Q, K, V of several pairs in
+    LDS (direct loads, per-tile counters, units of 32 query rows handed out dynamically)."""
+    torch, qf, ctx = gpu
+    B, H, N = bhn
+    plan = qf.qflash_plan_query(ctx.handle, B, H, N, 64, 64)       # (the plan assumes a 32 KiB table)
+    assert plan.kernel == 3 or B * H > 768, (bhn, plan.kernel)
+    Q, K, V, sQ, sK, _ = rand_case((B, H, N, 64), 900 + B + N, q_gain=1.0 + (N % 3) * 0.4)
+    p = oracle.derive_params(sQ, sK, 64)
+    check(gpu, Q, K, V, p, 64, label="whole CU %s pairs/wg %d" % (bhn, plan.pairs_per_workgroup))
+    if N in (197, 70):          # the coarse-score variant (x_shift > 0) and rounding to nearest
+        p2 = oracle.derive_params(sQ * 40.0, sK * 40.0, 64, out_round=1)
+        assert p2.x_shift > 0
+        check(gpu, Q, K, V, p2, 64, label="whole CU, x_shift %d" % p2.x_shift)
+
+
 @pytest.mark.parametrize("tile", [64, 128])
 def test_streamed_kernel_with_bias(gpu, tile):
     """d = 32 and a sequence too long for LDS: the kernel that streams KV tiles, with a bias in both
