@@ -62,18 +62,6 @@ __device__ __forceinline__ void count_up(int flag_addr) {
     const int one = 1;
     asm volatile("ds_add_u32 %0, %1" ::"v"(flag_addr), "v"(one) : "memory");
 }
-// Wait until at most n of this wavefront's loads are outstanding (the counter is an immediate of the
-// instruction; more than 15 outstanding later loads are simply all waited for).
-__device__ __attribute__((noinline)) void wait_own_loads(int n) {
-    switch (n) {
-#define QF_W(K_) case K_: asm volatile("s_waitcnt vmcnt(" #K_ ")" ::: "memory"); break;
-        QF_W(1) QF_W(2) QF_W(3) QF_W(4) QF_W(5) QF_W(6) QF_W(7) QF_W(8) QF_W(9) QF_W(10) QF_W(11) QF_W(12)
-        QF_W(13) QF_W(14) QF_W(15)
-#undef QF_W
-        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    }
-}
-
 #ifdef QF_TRACE
 // timestamps go to LDS (an instruction the compiler does not count, like the counters) and are copied out at the end
 #define QF_T(K_) do { if ((K_) < 16) { const unsigned long long t_ = __builtin_amdgcn_s_memrealtime(); \
@@ -106,8 +94,7 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
     const int lds0 = (int)(size_t)(lds_void)smem_cu;          // 0: checked by the host before the first launch
     const int tbytes = XM == kExpTable ? a.cu_table_lds : 0;
     const int kv_base = lds0 + tbytes;
-    // counters: [pair][tile]: wavefronts of the group whose loads for that tile have landed; [4 * hpw]: next unit;
-    // then [group]: wavefronts that have issued the loads of their first tile
+    // counters: [pair][tile]: wavefronts of the group whose loads for that tile have landed; [4 * hpw]: next unit
     const int cnt_base = kv_base + hpw * 3 * slot + 1024;
 #ifdef QF_TRACE
     const int trace_base = cnt_base + 4 * (5 * hpw + 1) + 8;
@@ -135,16 +122,22 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
     //      need.  Groups start one after the other (a short sleep), so that the memory system sees
     //      the requests of pair 0 first.  Pairs beyond the last group are taken by that group as
     //      well, after its own; they are only needed in the second round.
-    //      Loads complete in order, so before the first tile of its first unit a wavefront waits until
-    //      no more of its loads are outstanding than it has issued for later tiles and adds 1 to the
-    //      counter of (pair, tile 0); before the second tile it waits for all its loads (they have had
-    //      a whole tile's time) and adds 1 to the counters of all other tiles.  Before any tile of any
-    //      unit a wavefront waits until the counter of (pair, tile) has reached the size of the group.
+    //      A wavefront waits for its loads of the first tile right after issuing them and adds 1 to
+    //      the counter of (pair, tile 0); before the second tile of its first unit it waits for all its
+    //      loads (they have had a whole tile's time) and adds 1 to the counters of all other tiles.
+    //      Before any tile of any unit a wavefront waits until the counter of (pair, tile) has reached
+    //      the size of the group.
     const int last_group = (n_waves - 1) / nblk;
     const int my_group = wave / nblk;
     const int group_size = min(nblk, n_waves - my_group * nblk);
     const int member = wave - my_group * nblk;
     const int n_extra = my_group == last_group ? n_heads - 1 - my_group : 0;     // whole pairs
+    // A last group of fewer wavefronts than the others gets help with the first tile of its pair from
+    // group 0 (whose wavefronts issue their share after their own loads and report it with their
+    // other late loads, before the second tile of their first unit).
+    const int last_size = n_waves - last_group * nblk;
+    const bool small_last = last_group > 0 && last_size < nblk;
+    const bool helper = small_last && my_group == 0, helped = small_last && my_group == last_group;
     {
         // Lane part of the address inside a 16-row block: row lane / 4, 16-byte piece (lane % 4)
         // permuted by the row.  The last block of a tensor may reach beyond the sequence: its rows are
@@ -152,45 +145,46 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
         const int lrow = lane >> 2, piece = ((lane & 3) ^ ((lane >> 4) & 3)) << 4;
         const int off_norm = lrow * D + piece;
         const int off_last = (min(16 * (nb16 - 1) + lrow, N - 1) - 16 * (nb16 - 1)) * D + piece;
-        // first tile of the own pair (and the table), one group after the other
-        const int issued = cnt_base + 4 * (4 * hpw + 1);          // [group]: wavefronts that have issued their first-tile loads
-        if (my_group > 0) wait_count(issued + 4 * (my_group - 1), nblk);
+        // First tile of the own pair (and the table).  The other groups start when the first tile of
+        // group 0 has landed: the memory system shares its bandwidth evenly between whatever is in
+        // flight, so this is what lets group 0 start computing while the others are still loading.
+        if (my_group > 0) wait_count(cnt_base, nblk);
         if (XM == kExpTable && my_group == 0)
             for (int it = member; it < nt; it += group_size)
                 load_1k_to_lds((const int8_t*)hc.lut + 1024 * it, 16 * lane, lds0 + 1024 * it);
         const int x0 = min(8, 2 * nb16);                            // K/V block numbers of the first tile
-        auto load_q = [&](int h) {
+        auto load_q = [&](int h, int mi, int np) {
             const size_t head_off = (size_t)(head0 + h) * N * D;
-            for (int b = member; b < nb16; b += group_size)
+            for (int b = mi; b < nb16; b += np)
                 load_1k_to_lds(a.Q + head_off + 1024 * b, b == nb16 - 1 ? off_last : off_norm,
                                kv_base + (3 * h + 2) * slot + 1024 * b);
         };
-        auto load_kv = [&](int h, int x_lo, int x_hi) {
+        auto load_kv = [&](int h, int x_lo, int x_hi, int mi, int np) {
             const size_t head_off = (size_t)(head0 + h) * N * D;
-            const int first = x_lo + ((member - x_lo) % group_size + group_size) % group_size;
-            for (int x = first; x < x_hi; x += group_size) {
+            const int first = x_lo + ((mi - x_lo) % np + np) % np;
+            for (int x = first; x < x_hi; x += np) {
                 const int b = x >> 1;
                 load_1k_to_lds(((x & 1) ? a.V : a.K) + head_off + 1024 * b, b == nb16 - 1 ? off_last : off_norm,
                                kv_base + (3 * h + (x & 1)) * slot + 1024 * b);
             }
         };
-        load_q(my_group);
-        load_kv(my_group, 0, x0);
-        if (lane == 0) count_up(issued + 4 * my_group);
-        // the other tiles once every group has issued its first one; then further pairs
-        if (my_group < last_group) wait_count(issued + 4 * last_group, n_waves - last_group * nblk);
-        load_kv(my_group, x0, 2 * nb16);
+        // (a last group of few wavefronts shares the first tile of its pair with the group before it)
+        const int s0_np = helped ? group_size + nblk : group_size, s0_mi = helped ? nblk + member : member;
+        load_q(my_group, s0_mi, s0_np);
+        load_kv(my_group, 0, x0, s0_mi, s0_np);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (lane == 0) count_up(cnt_base + 4 * (4 * my_group));
+        // the other tiles, then further pairs, then the share of the next group's first tile
+        load_kv(my_group, x0, 2 * nb16, member, group_size);
         for (int e = 1; e <= n_extra; ++e) {
-            load_q(my_group + e);
-            load_kv(my_group + e, 0, 2 * nb16);
+            load_q(my_group + e, member, group_size);
+            load_kv(my_group + e, 0, 2 * nb16, member, group_size);
+        }
+        if (helper) {
+            load_q(last_group, member, nblk + last_size);
+            load_kv(last_group, 0, x0, member, nblk + last_size);
         }
     }
-    // own K/V loads of the own pair with number >= x, plus everything issued for further pairs
-    const int extra_loads = n_extra * ((nb16 - member + group_size - 1) / group_size + (2 * nb16 - member + group_size - 1) / group_size);
-    auto own_from = [&](int x) {
-        const int first = x + ((member - x) % group_size + group_size) % group_size;
-        return (first < 2 * nb16 ? (2 * nb16 - first + group_size - 1) / group_size : 0) + extra_loads;
-    };
     const int n_tiles = (N + BC - 1) / BC;
     [[maybe_unused]] int tk = 3;
     QF_T(2);
@@ -215,21 +209,18 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
         st.m = SB ? (int)((unsigned)kMInit + (unsigned)kAccBias) : kMInit;
         v4i qreg[2];
 #define QF_TILE(FULL_, FIRST_, J_, NV_, NG_)                                                               \
-        if (first_unit && (J_) <= 1) {                                                                     \
-            /* tile 0: the own loads of the first tile have landed; tile 1 (or a single tile): all of them */ \
-            const bool all = (J_) == 1 || n_tiles == 1;                                                    \
-            wait_own_loads(all ? 0 : own_from(2 * min(4, nb16)));                                          \
+        if (first_unit && (J_) == (n_tiles > 1 ? 1 : 0)) {                                                 \
+            /* second tile of the first unit (or its only one): all own loads have had a tile's time */   \
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                               \
             if (lane == 0) {                                                                               \
-                if ((J_) == 0) count_up(cnt_base + 4 * (4 * my_group));                                    \
-                if ((J_) == 1)                                                                             \
-                    for (int s = 1; s < n_tiles; ++s) count_up(cnt_base + 4 * (4 * my_group + s));         \
-                if (all)                                                                                   \
-                    for (int e = my_group + 1; e <= my_group + n_extra; ++e)                               \
-                        for (int s = 0; s < n_tiles; ++s) count_up(cnt_base + 4 * (4 * e + s));            \
+                if (helper) count_up(cnt_base + 4 * (4 * last_group));                                     \
+                for (int s = 1; s < n_tiles; ++s) count_up(cnt_base + 4 * (4 * my_group + s));             \
+                for (int e = my_group + 1; e <= my_group + n_extra; ++e)                                   \
+                    for (int s = 0; s < n_tiles; ++s) count_up(cnt_base + 4 * (4 * e + s));                \
             }                                                                                              \
         }                                                                                                  \
         if ((FIRST_) && XM == kExpTable && h != 0) wait_count(cnt_base, min(nblk, n_waves));               \
-        wait_count(cnt_base + 4 * (4 * h + (J_)), target);                                                 \
+        wait_count(cnt_base + 4 * (4 * h + (J_)), (J_) == 0 && small_last && h == last_group ? target + nblk : target); \
         if (FIRST_) QF_T(tk);                                                                              \
         if (FIRST_) {                                                                                      \
             _Pragma("unroll") for (int s = 0; s < 2; ++s)                                                  \

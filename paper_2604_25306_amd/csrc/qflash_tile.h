@@ -425,7 +425,8 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
     const int zz = z + rs;
     // The accumulators carry their offset (ReleaseConst); it is taken out, modulo 2^32, together
     // with the addition of 128 l.
-    const int bias_z = (int)(((128u * dsafe + (round_nearest ? (unsigned)st.l : 0u)) << z) - ((unsigned)kAccBias << zz));
+    int bias_z = (int)(((128u * dsafe + (round_nearest ? (unsigned)st.l : 0u)) << z) - ((unsigned)kAccBias << zz));
+    asm volatile("" : "+v"(bias_z));     // (kept as one addend: otherwise the offset is subtracted from every element first)
     // word[j]: features 8 j + 4 g + (0..3) of this lane's row, j = 4 t + a4
     unsigned word[4 * TB];
 #pragma unroll
