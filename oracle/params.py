@@ -26,7 +26,7 @@ LOG2_E = 1.4426950408889634  # log2(e) in IEEE double
 EXP_SHIFT = 32
 S_INV_MIN = 1 << 10
 S_INV_MAX = 1 << 18          # exclusive
-X_SHIFT_MAX = 13
+X_SHIFT_MAX = 16          # the range of k the interface of the method allows (the HIP library stops at 13)
 
 
 @dataclass(frozen=True)

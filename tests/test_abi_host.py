@@ -53,6 +53,10 @@ def test_params_agree_with_oracle_on_random_scales(lib):
             with pytest.raises(qf.QFlashError):
                 qf.qflash_params_from_scales(sQ, sK, 1.0, d)
             continue
+        if po.x_shift > 13:       # the oracle covers the whole range of the method, the library stops at k = 13
+            with pytest.raises(qf.QFlashError):
+                qf.qflash_params_from_scales(sQ, sK, 1.0, d)
+            continue
         pl = qf.qflash_params_from_scales(sQ, sK, 1.0, d)
         assert pl.astuple() == po.astuple(), (sQ, sK, d)
         n_ok += 1

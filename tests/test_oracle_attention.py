@@ -125,6 +125,73 @@ def test_two_tile_composition(N, tile):
     assert np.array_equal(out, np.clip(O2 // l2[..., None], -128, 127).astype(np.int8))
 
 
+@pytest.mark.parametrize("n_tiles,tile,order", [(3, 16, "up"), (5, 16, "up"), (10, 8, "up"), (4, 64, "up"),
+                                                (6, 16, "down"), (7, 16, "mixed")])
+def test_many_tile_composition(n_tiles, tile, order):
+    """The whole chain of Algorithm 1's inner loop, tile after tile, rebuilt in NumPy int64 from the
+    scores: running maximum, alpha from its change, ScaleRelease of denominator and numerator, the
+    tile's weights.  Keys are ordered so that the row maximum moves in every tile ("up"), never
+    after the first ("down"), or at random ("mixed"); the last tile is ragged."""
+    N = n_tiles * tile - 3
+    shape = (1, 2, N, 32)
+    rng = np.random.default_rng(77 + n_tiles)
+    Qf = np.abs(rng.standard_normal(shape)).astype(np.float32) * 1.5
+    Kf = np.abs(rng.standard_normal(shape)).astype(np.float32)
+    ramp = np.linspace(0.2, 1.0, N, dtype=np.float32)[None, None, :, None]
+    if order == "up":
+        Kf = Kf * ramp
+    elif order == "down":
+        Kf = Kf * ramp[:, :, ::-1]
+    else:
+        Kf = rng.standard_normal(shape).astype(np.float32)
+    Vf = rng.standard_normal(shape).astype(np.float32)
+    (Q, sQ), (K, sK), (V, _) = (quantize_per_tensor(x) for x in (Qf, Kf, Vf))
+    p = derive_params(sQ, sK, 32)
+    out, st = oracle.qflash_attention(Q, K, V, p, tile, return_state=True)
+    S = Q.astype(np.int64) @ K.astype(np.int64).transpose(0, 1, 3, 2)
+    Vi = V.astype(np.int64)
+    m = np.full(S.shape[:-1], -(1 << 21), dtype=np.int64)
+    l = np.zeros_like(m)
+    O = np.zeros(S.shape[:-1] + (32,), dtype=np.int64)
+    moved = []
+    for j in range(n_tiles):
+        Sj, Vj = S[..., j * tile:(j + 1) * tile], Vi[:, :, j * tile:(j + 1) * tile]
+        m_new = np.maximum(m, Sj.max(-1))
+        a16 = np.minimum((oracle.shift_exp2_np(m - m_new, p) * p.a_mul) >> 14, 65536)
+        Pj = oracle.requant_np(oracle.shift_exp2_np(Sj - m_new[..., None], p), p)
+        l = ((l * a16) >> 16) + Pj.sum(-1)
+        O = ((O * a16[..., None]) >> 16) + Pj @ Vj
+        if j > 0:
+            moved.append(float((m_new > m).mean()))
+        m = m_new
+    if order == "up":
+        assert min(moved) > 0.7, moved            # the maximum moves in every tile for most rows
+    if order == "down":
+        assert max(moved) < 0.3, moved
+    assert np.array_equal(st["m"], m) and np.array_equal(st["l"], l) and np.array_equal(st["O_acc"], O)
+    assert np.array_equal(out, np.clip(O // l[..., None], -128, 127).astype(np.int8))
+
+
+def test_initial_maximum_survives_in_a_fully_excluded_row():
+    """Algorithm 1 starts the running maximum at -2^21; a row whose every key is excluded never
+    updates it (and yields zeros), in one tile and in several."""
+    shape = (1, 2, 40, 32)
+    Q, K, V, sQ, sK, _ = rand_case(shape, 5)
+    p = derive_params(sQ, sK, 32)
+    bias = np.zeros((1, 1, 40, 40), dtype=np.int32)
+    bias[0, 0, 7, :] = EXCLUDED
+    bias[0, 0, 12, :39] = EXCLUDED              # one key left: an ordinary row
+    for tile in (64, 16):
+        out, st = oracle.qflash_attention(Q, K, V, p, tile, bias=bias, return_state=True)
+        assert np.all(st["m"][:, :, 7] == -(1 << 21)) and np.all(st["l"][:, :, 7] == 0)
+        assert np.all(out[:, :, 7] == 0)
+        S = Q.astype(np.int64) @ K.astype(np.int64).transpose(0, 1, 3, 2)
+        assert np.array_equal(st["m"][:, :, 12], S[:, :, 12, 39])
+        assert np.array_equal(out[:, :, 12], V[:, :, 39])          # a single weight: the value row itself
+        others = [i for i in range(40) if i not in (7, 12)]
+        assert np.array_equal(st["m"][:, :, others], S[:, :, others].max(-1))
+
+
 def test_uniform_scores_give_floor_of_mean():
     """K = 0: all scores equal, all weights equal, every alpha is 1.0 -> out = floor(mean V)."""
     rng = np.random.default_rng(9)
