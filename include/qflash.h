@@ -77,12 +77,34 @@ int qflash_create(qflash_ctx** out, int device_id);
  * score (Algorithm 2 followed by Eq. 10) from a table of that same function held in LDS when the
  * table is small enough (about 8 * s_inv / 2^x_shift bytes, up to 40 KiB); 0 always evaluates
  * Algorithm 2 arithmetically.  Both give identical bits.  A table is built on the GPU, once per
- * set of constants and stream (first call with them; up to 32 per context, never rewritten; when
- * they are used up later constants take the arithmetic mode).
+ * set of constants and stream (first call with them) and kept in one of 32 slots of the context.
+ * When all are taken, the least recently used one is rebuilt for the new constants; the building
+ * kernel waits on the GPU (never on the host) for what has been enqueued so far on the stream that
+ * read the old table.  A call on a stream that is being captured into a HIP graph builds nothing:
+ * it uses a table only if an earlier call on that stream has built it (such a table is then kept
+ * for good, because the graph reads it on every replay) and computes arithmetically otherwise.
  * Errors: NULL, CTX, PARAM (unknown key or value).
  */
 #define QFLASH_CFG_EXP_TABLE 1
 int qflash_configure(qflash_ctx* ctx, int key, int value);
+
+/*
+ * State of the context's table cache and what the last call through it did (host only; for
+ * callers who want to know whether their constants keep the look-up mode, and for tests).
+ *   slots_total, slots_in_use, slots_pinned (read by a captured graph: never rebuilt), evictions
+ *   (slots rebuilt for other constants so far); last_weight_mode: QFLASH_WEIGHTS_ARITHMETIC, _TABLE
+ *   (every head read its table) or _MIXED (per-head constants of which only some had a table) of the
+ *   last qflash_attention / _per_head / _packed_bias call; last_kernel: as qflash_plan_info.kernel.
+ * Errors: NULL, CTX.
+ */
+#define QFLASH_WEIGHTS_ARITHMETIC 0
+#define QFLASH_WEIGHTS_TABLE      1
+#define QFLASH_WEIGHTS_MIXED      2
+typedef struct {
+    int32_t slots_total, slots_in_use, slots_pinned, evictions;
+    int32_t last_weight_mode, last_kernel, reserved[2];
+} qflash_cache_info;
+int qflash_cache_query(qflash_ctx* ctx, qflash_cache_info* out /* host */);
 
 /*
  * One fused attention forward pass (Algorithm 1), enqueued on `hip_stream`; returns without
@@ -105,9 +127,10 @@ int qflash_configure(qflash_ctx* ctx, int key, int value);
  *   hip_stream  a hipStream_t of the context's device (NULL = the default stream).
  *
  * All buffers must stay valid until the stream has executed the work.  Calls on one context
- * from several host threads are allowed (the context's table cache is guarded by a lock).  The
- * first call with new constants on a stream also enqueues a small table-building kernel on that
- * stream; a stream handle must not be reused for a new stream while its context lives.
+ * from several host threads are allowed (the context's table cache is guarded by a lock of its own;
+ * contexts do not wait for one another).  The first call with new constants on a stream also
+ * enqueues a small table-building kernel on that stream; a stream handle must not be reused for a
+ * new stream while its context lives.
  * Errors: CTX, NULL, SHAPE, TILE, PARAM, ALIGN, DEVICE, LAUNCH.  On error nothing is enqueued.
  */
 int qflash_attention(qflash_ctx* ctx,
@@ -140,7 +163,7 @@ int qflash_attention_static(qflash_ctx* ctx,
                             const qflash_params* p, void* hip_stream);
 
 /*
- * The same pass with per-head quantisation (Section 3.2 and Appendix C3: per-tensor and per-head
+ * The same pass with per-head quantisation (Section 3.3 and Appendix B.3: per-tensor and per-head
  * are the granularities under which the integer running maximum still compares like with like).
  * p points to H entries (host); head h of every batch element uses p[h], and its output has the
  * scale s_V of that head.  All entries must share out_round.  H <= QFLASH_MAX_PARAM_HEADS.
@@ -202,7 +225,7 @@ int qflash_attention_packed_bias(qflash_ctx* ctx,
  *   O           device, int8, [B,H,N,d]; scale s_V as reported in *info.
  *   info        device or NULL; receives the scales, the constants used and a status: QFLASH_OK,
  *               or QFLASH_ERR_PARAM when the scales fall outside the supported window (O is then
- *               unspecified; nothing out of bounds is touched).
+ *               all zeros, with or without info).
  *   workspace   device scratch of at least qflash_dynamic_workspace_bytes(B,H,N,d) bytes, 16-byte
  *               aligned, caller-owned; it holds the int8 copies of Q, K, V among other things and
  *               must stay untouched until the stream has executed the work.  The call allocates

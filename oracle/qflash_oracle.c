@@ -151,7 +151,7 @@ static int attention_impl(const int8_t *Q, const int8_t *K, const int8_t *V,
 #pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad_total)
     for (int bh = 0; bh < B * H; ++bh) {
         const int b = bh / H, h = bh % H;
-        /* per-tensor constants, or those of head h (Section 3.2 / Appendix C3: per-head scales) */
+        /* per-tensor constants, or those of head h (Section 3.3 / Appendix B.3: per-head scales) */
         const oracle_params *p = p_per_head ? p_all + h : p_all;
         const int8_t *Qh = Q + (size_t)bh * N * d;
         const int8_t *Kh = K + (size_t)bh * N * d;
@@ -261,7 +261,7 @@ int oracle_qflash_attention(const int8_t *Q, const int8_t *K, const int8_t *V,
 
 /*
  * The same with one set of integer constants per head: p[h] serves every (b, h) pair of head h
- * (per-head quantisation, Section 3.2 and Appendix C3: Q, K and V of a head share one scale
+ * (per-head quantisation, Section 3.3 and Appendix B.3: Q, K and V of a head share one scale
  * each, so the running maximum still compares like with like).  The output of head h has scale
  * s_V of that head.  Everything else as above.
  */

@@ -18,7 +18,7 @@ EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qf
            "qflash_attention_static",
            "qflash_attention_per_head", "qflash_dynamic_workspace_bytes", "qflash_attention_dynamic",
            "qflash_packed_bias_bytes", "qflash_pack_bias", "qflash_attention_packed_bias",
-           "qflash_plan_query", "qflash_plan_unit",
+           "qflash_plan_query", "qflash_plan_unit", "qflash_cache_query",
            "qflash_destroy", "qflash_strerror"]
 
 MAX_PARAM_HEADS = 64
@@ -48,6 +48,16 @@ class DynamicInfo(ctypes.Structure):
     """Mirror of ``qflash_dynamic_info`` (what the dynamic entry point reports, in device memory)."""
     _fields_ = [("sQ", ctypes.c_double), ("sK", ctypes.c_double), ("sV", ctypes.c_double),
                 ("params", QFlashParams), ("status", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class CacheInfo(ctypes.Structure):
+    """Mirror of ``qflash_cache_info`` (state of a context's table cache, mode of its last launch)."""
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "slots_total", "slots_in_use", "slots_pinned", "evictions", "last_weight_mode", "last_kernel")] + \
+        [("reserved", ctypes.c_int32 * 2)]
+
+
+WEIGHTS_ARITHMETIC, WEIGHTS_TABLE, WEIGHTS_MIXED = 0, 1, 2
 
 
 class PlanInfo(ctypes.Structure):
@@ -99,6 +109,8 @@ def load_library():
         lib.qflash_plan_unit.argtypes = [ctypes.POINTER(PlanInfo), ci]
         lib.qflash_configure.restype = ci
         lib.qflash_configure.argtypes = [vp, ci, ci]
+        lib.qflash_cache_query.restype = ci
+        lib.qflash_cache_query.argtypes = [vp, ctypes.POINTER(CacheInfo)]
         lib.qflash_destroy.restype = ci
         lib.qflash_destroy.argtypes = [vp]
         lib.qflash_strerror.restype = ctypes.c_char_p
@@ -262,6 +274,14 @@ def qflash_plan_query(ctx: Optional[int], B: int, H: int, N: int, d: int, kv_til
     return info
 
 
+def qflash_cache_query(ctx: int) -> CacheInfo:
+    info = CacheInfo()
+    rc = load_library().qflash_cache_query(ctypes.c_void_p(ctx), ctypes.byref(info))
+    if rc != 0:
+        raise QFlashError(rc, "qflash_cache_query")
+    return info
+
+
 def qflash_plan_unit(plan: PlanInfo, workgroup: int) -> int:
     return int(load_library().qflash_plan_unit(ctypes.byref(plan), int(workgroup)))
 
@@ -306,6 +326,9 @@ class Context:
 
     def configure(self, key: int, value: int):
         qflash_configure(self.handle, key, value)
+
+    def cache_info(self) -> CacheInfo:
+        return qflash_cache_query(self.handle)
 
     def attention(self, Q, K, V, O, params, kv_tile, bias=None, stream=None):
         """``params``: one QFlashParams (per-tensor scales) or a sequence of H (per-head scales)."""

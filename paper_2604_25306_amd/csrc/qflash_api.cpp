@@ -14,13 +14,17 @@
 #include "qflash_internal.h"
 #include "qflash_derive.h"
 
-// One immutable weight table.  A slot is written once (by a kernel enqueued on `stream`) and only
-// ever used by launches on that same stream, so stream order alone makes it safe; it is never
-// rewritten, so captured graphs and in-flight kernels can keep reading it.
+// One weight table.  A slot is written by a kernel enqueued on `stream` and only ever read by
+// launches on that same stream, so stream order alone makes the first use safe.  When all slots are
+// taken, the least recently used one is rebuilt for new constants: the building kernel then waits,
+// on the GPU, for everything enqueued so far on the stream that read the old table.  A slot that
+// a stream under capture has used is never rebuilt: a captured graph keeps reading it.
 struct TableSlot {
     int32_t key[5];   // x_shift, s_inv, exp_mul, p_mul, p_shift
     void* stream;
     int n, n_padded, x_p;
+    uint64_t last_use;   // value of the context's launch counter at the last launch that read it
+    bool pinned;         // read under stream capture
 };
 
 constexpr int kPlanQueryTableBytes = 32 * 1024;   // table size qflash_plan_query assumes (it is not given constants)
@@ -44,6 +48,12 @@ struct qflash_ctx {
     uint8_t* scratch_ptr; // device address of `scratch` on this context's GPU, or nullptr
     int n_slots;          // slots in use
     TableSlot slots[kTableSlots];
+    std::mutex mu;        // guards the table cache and the options; held while a launch that reads the cache is enqueued
+    uint64_t launches;    // launch counter (age of the slots)
+    hipEvent_t evict_ev;  // marks "everything enqueued so far" on the stream of a slot about to be rebuilt
+    int evictions;        // slots rebuilt for other constants so far
+    int last_mode;        // weight mode of the last launch through the cache: QFLASH_WEIGHTS_*
+    int last_kernel;      // kernel family of the last launch (as qflash_plan_info.kernel)
 };
 
 namespace {
@@ -92,11 +102,20 @@ extern "C" int qflash_create(qflash_ctx** out, int device_id) {
     c->use_table = 1;
     c->n_slots = 0;
     c->tables = nullptr;
+    c->launches = 0;
+    c->evictions = 0;
+    c->last_mode = QFLASH_WEIGHTS_ARITHMETIC;
+    c->last_kernel = 0;
+    c->evict_ev = nullptr;
     int cur = -1;
     const bool switched = hipGetDevice(&cur) == hipSuccess && cur != device_id && hipSetDevice(device_id) == hipSuccess;
     if (hipMalloc((void**)&c->tables, (size_t)kTableSlots * kTableMaxBytes) != hipSuccess) {
         (void)hipGetLastError();
         c->tables = nullptr;   // the arithmetic mode needs no tables
+    }
+    if (hipEventCreateWithFlags(&c->evict_ev, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        c->evict_ev = nullptr;     // without it a full cache is never recycled
     }
     // Address of this device's copy of the static table memory (the context's device is current).
     c->scratch_ptr = nullptr;
@@ -125,15 +144,19 @@ extern "C" int qflash_destroy(qflash_ctx* ctx) {
     if (ctx->tables) {
         if (hipFree(ctx->tables) != hipSuccess) (void)hipGetLastError();
     }
+    if (ctx->evict_ev && hipEventDestroy(ctx->evict_ev) != hipSuccess) (void)hipGetLastError();
     delete ctx;
     return QFLASH_OK;
 }
 
 extern "C" int qflash_configure(qflash_ctx* ctx, int key, int value) {
     if (!ctx) return QFLASH_ERR_NULL;
-    std::lock_guard<std::mutex> lk(g_mu);
-    if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+    }
     if (key != QFLASH_CFG_EXP_TABLE || (value != 0 && value != 1)) return QFLASH_ERR_PARAM;
+    std::lock_guard<std::mutex> lk(ctx->mu);
     ctx->use_table = value;
     return QFLASH_OK;
 }
@@ -170,6 +193,9 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         lds_limit = ctx->lds_limit;
         n_cu = ctx->n_cu;
         scratch_ptr = ctx->scratch_ptr;
+    }
+    {
+        std::lock_guard<std::mutex> lk(ctx->mu);
         table_wanted = ctx->use_table != 0;
     }
     if (!Q || !K || !V || !O || (!p && !hc_dev)) return QFLASH_ERR_NULL;
@@ -261,11 +287,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         // Constants made on the GPU: so is the table, by the quantising kernel ahead of this one on
         // the stream, which also decides whether there is one (mode 3 reads that decision per
         // workgroup; without mode 3 the table is simply not looked at).
-        bool use_table;
-        {
-            std::lock_guard<std::mutex> lk(g_mu);
-            use_table = ctx->use_table != 0;
-        }
+        const bool use_table = table_wanted;
         if (use_table && dyn_table && a.resident && !bias && table_fits(a, d, kTableMaxBytes, lds_limit)) {
             a.exp_mode = 3;
             a.lut_bytes_max = kTableMaxBytes;
@@ -283,8 +305,20 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
             a.lut_bytes_max = static_np;
         }
     } else {
-        std::lock_guard<std::mutex> lk(g_mu);
+        // The context's lock is held until the attention kernel has been enqueued: a slot this launch
+        // reads must not be handed to other constants by another host thread in between.
+        std::unique_lock<std::mutex> lk(ctx->mu);
         const bool allowed = ctx->use_table && ctx->tables && a.resident && !(per_head && a.heads_per_wg > 1 && !a.same_head);
+        // A stream under capture records the kernels instead of running them: a table built now would
+        // be read, by eager launches with the same constants, before it has ever been written.  Such a
+        // call only uses tables that already exist (and pins them, since the graph keeps reading them).
+        bool capturing = false;
+        {
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess) { (void)hipGetLastError(); capturing = true; }
+            else capturing = cs != hipStreamCaptureStatusNone;
+        }
+        const uint64_t now = ++ctx->launches;
         int xp[kQflashMaxParamHeads], np_[kQflashMaxParamHeads], max_bytes = 0, n_with = 0;
         bool has[kQflashMaxParamHeads];
         for (int h = 0; h < n_p; ++h) {
@@ -306,19 +340,51 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
                     slot = i;
                     break;
                 }
-            if (slot < 0 && ctx->n_slots < kTableSlots) {
-                // The builder is enqueued under the lock, so no other host thread can enqueue a
-                // reader of this slot on the same stream ahead of it.
-                uint8_t* tbl = ctx->tables + (size_t)ctx->n_slots * kTableMaxBytes;
-                rc = qflash_launch_build_table(tbl, xp[h] + 1, np_[h], xp[h], a.hc[h], hip_stream);
-                if (rc == 0) {
-                    slot = ctx->n_slots++;
-                    TableSlot& t = ctx->slots[slot];
-                    std::memcpy(t.key, key, sizeof key);
-                    t.stream = hip_stream; t.n = xp[h] + 1; t.n_padded = np_[h]; t.x_p = xp[h];
+            if (slot < 0 && !capturing) {
+                int victim = -1;
+                if (ctx->n_slots < kTableSlots) {
+                    victim = ctx->n_slots;
+                } else if (ctx->evict_ev) {
+                    // least recently used slot that no graph reads and this launch does not need
+                    for (int i = 0; i < kTableSlots; ++i)
+                        if (!ctx->slots[i].pinned && ctx->slots[i].last_use < now &&
+                            (victim < 0 || ctx->slots[i].last_use < ctx->slots[victim].last_use))
+                            victim = i;
+                    if (victim >= 0) {
+                        // the builder must not overtake the launches that still read the old table
+                        bool ordered = ctx->slots[victim].stream == hip_stream;
+                        if (!ordered) {
+                            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+                            const hipStream_t old = (hipStream_t)ctx->slots[victim].stream;
+                            if (hipStreamIsCapturing(old, &cs) == hipSuccess && cs == hipStreamCaptureStatusNone &&
+                                hipEventRecord(ctx->evict_ev, old) == hipSuccess &&
+                                hipStreamWaitEvent((hipStream_t)hip_stream, ctx->evict_ev, 0) == hipSuccess)
+                                ordered = true;
+                            else
+                                (void)hipGetLastError();
+                        }
+                        if (!ordered) victim = -1;
+                        else ++ctx->evictions;
+                    }
+                }
+                if (victim >= 0) {
+                    // The builder is enqueued under the lock, so no other host thread can enqueue a
+                    // reader of this slot on the same stream ahead of it.
+                    uint8_t* tbl = ctx->tables + (size_t)victim * kTableMaxBytes;
+                    rc = qflash_launch_build_table(tbl, xp[h] + 1, np_[h], xp[h], a.hc[h], hip_stream);
+                    if (rc == 0) {
+                        slot = victim;
+                        if (victim == ctx->n_slots) ++ctx->n_slots;
+                        TableSlot& t = ctx->slots[slot];
+                        std::memcpy(t.key, key, sizeof key);
+                        t.stream = hip_stream; t.n = xp[h] + 1; t.n_padded = np_[h]; t.x_p = xp[h];
+                        t.pinned = false;
+                    }
                 }
             }
-            if (slot < 0) { has[h] = false; continue; }     // no slot left: this head computes
+            if (slot < 0) { has[h] = false; continue; }     // no slot to be had: this head computes
+            ctx->slots[slot].last_use = now;
+            if (capturing) ctx->slots[slot].pinned = true;
             a.hc[h].lut = ctx->tables + (size_t)slot * kTableMaxBytes;
             a.hc[h].lut_bytes = np_[h];
             a.hc[h].lut_xp = xp[h];
@@ -333,6 +399,13 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         } else {
             for (int h = 0; h < n_p; ++h) { a.hc[h].lut = nullptr; a.hc[h].lut_bytes = 0; a.hc[h].lut_xp = 0; }
         }
+        if (rc == 0) rc = a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream) : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+        ctx->last_mode = a.exp_mode == 2 ? QFLASH_WEIGHTS_TABLE : a.exp_mode == 3 ? QFLASH_WEIGHTS_MIXED : QFLASH_WEIGHTS_ARITHMETIC;
+        ctx->last_kernel = a.cu_mode ? 3 : !a.resident ? 0 : a.ring ? 2 : 1;
+        lk.unlock();
+        if (cur != device) (void)hipSetDevice(cur);
+        if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
+        return QFLASH_OK;
     }
     if (rc == 0) rc = a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream) : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
@@ -409,6 +482,23 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
     return QFLASH_OK;
 }
 
+extern "C" int qflash_cache_query(qflash_ctx* ctx, qflash_cache_info* out) {
+    if (!ctx || !out) return QFLASH_ERR_NULL;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+    }
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    std::memset(out, 0, sizeof *out);
+    out->slots_total = ctx->tables ? kTableSlots : 0;
+    out->slots_in_use = ctx->n_slots;
+    for (int i = 0; i < ctx->n_slots; ++i) out->slots_pinned += ctx->slots[i].pinned ? 1 : 0;
+    out->evictions = ctx->evictions;
+    out->last_weight_mode = ctx->last_mode;
+    out->last_kernel = ctx->last_kernel;
+    return QFLASH_OK;
+}
+
 extern "C" int qflash_plan_unit(const qflash_plan_info* plan, int workgroup) {
     if (!plan || workgroup < 0 || workgroup >= plan->workgroups) return -1;
     if (plan->kernel == 3) return workgroup;
@@ -479,11 +569,13 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
                                         qflash_dynamic_info* info, void* workspace, size_t workspace_bytes,
                                         void* hip_stream) {
     if (!ctx) return QFLASH_ERR_NULL;
-    int device;
+    int device, lds_limit, n_cu;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
         device = ctx->device;
+        lds_limit = ctx->lds_limit;
+        n_cu = ctx->n_cu;
     }
     if (!Qf || !Kf || !Vf || !O || !workspace) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
@@ -494,6 +586,14 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
     if (out_round != 0 && out_round != 1) return QFLASH_ERR_PARAM;
     if (((uintptr_t)Qf | (uintptr_t)Kf | (uintptr_t)Vf | (uintptr_t)O | (uintptr_t)workspace) & 15u) return QFLASH_ERR_ALIGN;
     if (info && ((uintptr_t)info & 7u)) return QFLASH_ERR_ALIGN;
+    {
+        // everything the attention launch would refuse is refused here, before the quantising kernels
+        // are enqueued
+        QflashKernelArgs probe;
+        std::memset(&probe, 0, sizeof probe);
+        probe.B = B; probe.H = H; probe.N = N; probe.bias_B = 1; probe.bias_H = 1; probe.n_cu = n_cu;
+        if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &probe) != 0) return QFLASH_ERR_SHAPE;
+    }
 
     const size_t n = (size_t)B * H * N * d;        // a multiple of 32
     int8_t* ws = (int8_t*)workspace;

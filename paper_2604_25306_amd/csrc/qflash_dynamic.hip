@@ -69,12 +69,14 @@ __device__ void derive_on_device(const float am[3], double sqrt_d, int out_round
         if (!qflash_fill_head_consts(p, hc)) status = QFLASH_ERR_PARAM;
     }
     if (status != QFLASH_OK) {
-        // Scales outside the supported window: keep the attention kernel on safe constants (those
-        // of a mid-range scale) so that it runs without touching anything it should not; its output
-        // is then meaningless and the status says so.
+        // Scales outside the supported window: the attention kernel runs on safe constants (those
+        // of a mid-range scale) with the requantisation multiplier set to 0, so that every weight is
+        // 0, every denominator is 0 and the output is all zeros (Algorithm 1 with l = 0); the status
+        // says why.
         (void)qflash_derive_params(0.03, 0.03, sqrt_d, &p);
         p.out_round = out_round;
         (void)qflash_fill_head_consts(p, hc);
+        hc->p_mul = 0;
     }
     if (info) {
         info->sQ = s[0]; info->sK = s[1]; info->sV = s[2];

@@ -46,6 +46,8 @@
 #include "qflash_internal.h"
 #include "qflash_device.h"
 
+#include <mutex>
+
 #include "qflash_tile.h"
 
 namespace {
@@ -589,12 +591,21 @@ template <int D, int BC, int BIAS, bool NARROW, int XM>
 int launch_resident(const QflashKernelArgs& a, size_t lds_bytes, int lds_limit, int threads, hipStream_t stream) {
     const dim3 grid((unsigned)(8 * a.units_per_xcd));
     auto kern = qflash_fwd_resident<D, BC, BIAS, NARROW, XM>;
-    static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; a race only repeats it
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit) != hipSuccess)
-            return (int)hipGetLastError();
-        attr_set = true;
-    }
+    // once per process and device: raise the dynamic LDS limit of this kernel, and make sure that it
+    // has no static LDS in front of the dynamic one (the index into the weight table is used as an
+    // LDS address)
+    static std::once_flag once[kQflashMaxDevices];
+    static int status[kQflashMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kQflashMaxDevices) return (int)hipErrorInvalidDevice;
+    std::call_once(once[dev], [&] {
+        hipFuncAttributes fa;
+        hipError_t e = hipFuncGetAttributes(&fa, (const void*)kern);
+        if (e == hipSuccess && fa.sharedSizeBytes != 0) e = hipErrorInvalidValue;
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
+        status[dev] = (int)e;
+    });
+    if (status[dev] != 0) return status[dev];
     hipLaunchKernelGGL(kern, grid, dim3((unsigned)threads), lds_bytes, stream, a);
     return (int)hipGetLastError();
 }

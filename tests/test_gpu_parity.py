@@ -501,6 +501,7 @@ def test_dynamic_degenerate_and_out_of_window(gpu):
         oracle.qflash_attention_dynamic(Kf * 1e-6, Kf * 1e-6, Vf, 64)
     out, inf, _ = run_dynamic(gpu, Kf * 1e-6, Kf * 1e-6, Vf, 64)
     assert inf.status == qf.ERR["PARAM"]
+    assert not out.any(), "scales outside the window: the output must be all zeros"
     # argument errors
     dev = torch.device("cuda:0")
     t = torch.zeros(shape, dtype=torch.float32, device=dev)
@@ -627,24 +628,109 @@ def test_graph_capture_and_replay(gpu):
 
 
 def test_table_cache_many_constants_and_streams(gpu):
-    """More distinct constants than the context has table slots (later ones fall back to the
-    arithmetic mode), and the same constants on two streams (each builds its own table)."""
-    torch, qf, ctx = gpu
-    rng = np.random.default_rng(12)
-    shape = (1, 2, 100, 64)
-    Q = rng.integers(-127, 128, size=shape).astype(np.int8)
-    K = rng.integers(-127, 128, size=shape).astype(np.int8)
-    V = rng.integers(-127, 128, size=shape).astype(np.int8)
-    s2 = torch.cuda.Stream()
-    for j in range(40):
-        p = oracle.derive_params(0.03 + 0.001 * j, 0.04, 64)
+    """Far more distinct constants than the context has table slots (a 12-layer, 12-head model with
+    per-head constants has 144): the least recently used tables are rebuilt, every call keeps the
+    look-up mode and every result equals the oracle's; the same constants on two streams (each
+    builds its own table); eviction across streams."""
+    torch, qf, _ = gpu
+    ctx = qf.Context(0)                       # a cache of its own, in its initial state
+    try:
+        rng = np.random.default_rng(12)
+        shape = (1, 2, 197, 64)
+        Q = rng.integers(-127, 128, size=shape).astype(np.int8)
+        K = rng.integers(-127, 128, size=shape).astype(np.int8)
+        V = rng.integers(-127, 128, size=shape).astype(np.int8)
+        g2 = (torch, qf, ctx)
+        s2 = torch.cuda.Stream()
+        for j in range(144):
+            p = oracle.derive_params(0.03 + 0.0002 * j, 0.04, 64)
+            out = run_gpu(g2, Q, K, V, p, 64, stream=s2.cuda_stream if j % 5 == 4 else None)
+            ci = ctx.cache_info()
+            assert ci.last_weight_mode == qf.WEIGHTS_TABLE, (j, ci.last_weight_mode)
+            if j % 9 == 0 or j > 138:
+                assert np.array_equal(out, oracle.qflash_attention(Q, K, V, p, 64)), j
+        ci = ctx.cache_info()
+        assert ci.slots_in_use == ci.slots_total == 32 and ci.evictions == 144 - 32 and ci.slots_pinned == 0
+        # the first constants again (their table was rebuilt for others long ago), on both streams
+        p = oracle.derive_params(0.03, 0.04, 64)
         ref = oracle.qflash_attention(Q, K, V, p, 64)
-        assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64), ref), j
-        if j < 3:
-            assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64, stream=s2.cuda_stream), ref), j
-    # and the first constants still work after the cache is full
-    p = oracle.derive_params(0.03, 0.04, 64)
-    assert np.array_equal(run_gpu(gpu, Q, K, V, p, 64), oracle.qflash_attention(Q, K, V, p, 64))
+        assert np.array_equal(run_gpu(g2, Q, K, V, p, 64), ref)
+        assert np.array_equal(run_gpu(g2, Q, K, V, p, 64, stream=s2.cuda_stream), ref)
+        assert ctx.cache_info().last_weight_mode == qf.WEIGHTS_TABLE
+        # per-head constants, 12 heads: one table each, all found again on the second call
+        shape = (2, 12, 197, 64)
+        Q, K, V = (rng.integers(-127, 128, size=shape).astype(np.int8) for _ in range(3))
+        ps = [oracle.derive_params(0.05 + 0.001 * h, 0.045, 64) for h in range(12)]      # none of them seen before
+        ref = oracle.qflash_attention(Q, K, V, ps, 64)
+        for rep in range(2):
+            assert np.array_equal(run_gpu(g2, Q, K, V, ps, 64), ref), rep
+            assert ctx.cache_info().last_weight_mode == qf.WEIGHTS_TABLE
+        assert ctx.cache_info().evictions == 144 - 32 + 2 + 12
+        # with the table switched off the same call reports the arithmetic mode
+        ctx.configure(qf.CFG_EXP_TABLE, 0)
+        assert np.array_equal(run_gpu(g2, Q, K, V, ps, 64), ref)
+        assert ctx.cache_info().last_weight_mode == qf.WEIGHTS_ARITHMETIC
+    finally:
+        ctx.close()
+
+
+def test_capture_before_any_eager_call(gpu):
+    """A stream is captured into a HIP graph before the context has ever seen the constants: the
+    captured call must not leave a table behind that only exists once the graph has run (an eager
+    call with the same constants right after the capture would read it unwritten).  Captured call:
+    arithmetic; eager call afterwards: builds its table; every replay and the eager call equal the
+    oracle.  A second graph captured after the eager call reads the table and pins it."""
+    torch, qf, _ = gpu
+    dev = torch.device("cuda:0")
+    ctx = qf.Context(0)
+    try:
+        rng = np.random.default_rng(31)
+        shape = (2, 3, 197, 64)
+        Q, K, V = (rng.integers(-127, 128, size=shape).astype(np.int8) for _ in range(3))
+        p = oracle.derive_params(0.031, 0.041, 64)
+        lp = lib_params(qf, p)
+        ref = oracle.qflash_attention(Q, K, V, p, 64)
+        q, k, v = (torch.from_numpy(x).to(dev) for x in (Q, K, V))
+        o_graph, o_eager = torch.zeros_like(q), torch.zeros_like(q)
+        # kernel attributes are set on first use of a kernel variant: do that outside the capture,
+        # with other constants and the table switched off (the arithmetic variant is what is captured)
+        ctx.configure(qf.CFG_EXP_TABLE, 0)
+        ctx.attention(q, k, v, o_eager, lib_params(qf, oracle.derive_params(0.05, 0.05, 64)), 64)
+        ctx.configure(qf.CFG_EXP_TABLE, 1)
+        torch.cuda.synchronize()
+        assert ctx.cache_info().slots_in_use == 0
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.attention(q, k, v, o_graph, lp, 64)
+        ci = ctx.cache_info()
+        assert ci.slots_in_use == 0 and ci.last_weight_mode == qf.WEIGHTS_ARITHMETIC
+        # eager call on the same stream, same constants, before the graph has ever run
+        with torch.cuda.stream(side):
+            ctx.attention(q, k, v, o_eager, lp, 64)
+        torch.cuda.synchronize()
+        assert np.array_equal(o_eager.cpu().numpy(), ref)
+        ci = ctx.cache_info()
+        assert ci.slots_in_use == 1 and ci.last_weight_mode == qf.WEIGHTS_TABLE and ci.slots_pinned == 0
+        for rep in range(3):
+            o_graph.fill_(0x22)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(o_graph.cpu().numpy(), ref), rep
+        graph2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph2, stream=side):
+            ctx.attention(q, k, v, o_graph, lp, 64)
+        ci = ctx.cache_info()
+        assert ci.last_weight_mode == qf.WEIGHTS_TABLE and ci.slots_pinned == 1
+        o_graph.fill_(0x33)
+        torch.cuda.synchronize()
+        graph2.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(o_graph.cpu().numpy(), ref)
+        del graph, graph2
+    finally:
+        ctx.close()
 
 
 def test_concurrent_host_threads(gpu):
