@@ -21,6 +21,8 @@ EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qf
            "qflash_plan_query", "qflash_plan_unit", "qflash_cache_query",
            "qflash_destroy", "qflash_strerror"]
 
+PEAKS_EXPORTS = ["qflash_peaks_mfma_i8", "qflash_peaks_mfma_i8_ops", "qflash_peaks_copy"]   # include/qflash_peaks.h
+
 MAX_PARAM_HEADS = 64
 
 CFG_EXP_TABLE = 1
@@ -113,6 +115,12 @@ def load_library():
         lib.qflash_cache_query.argtypes = [vp, ctypes.POINTER(CacheInfo)]
         lib.qflash_destroy.restype = ci
         lib.qflash_destroy.argtypes = [vp]
+        lib.qflash_peaks_mfma_i8.restype = ci
+        lib.qflash_peaks_mfma_i8.argtypes = [ci, ci, vp, ctypes.c_size_t, vp]
+        lib.qflash_peaks_mfma_i8_ops.restype = dbl
+        lib.qflash_peaks_mfma_i8_ops.argtypes = [ci, ci]
+        lib.qflash_peaks_copy.restype = ci
+        lib.qflash_peaks_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.qflash_strerror.restype = ctypes.c_char_p
         lib.qflash_strerror.argtypes = [ci]
         _lib = lib
@@ -316,6 +324,32 @@ def qflash_attention_dynamic(ctx: int, Qf, Kf, Vf, O, kv_tile: int, workspace, i
         ctypes.c_void_p(stream))
     if rc != 0:
         raise QFlashError(rc, "qflash_attention_dynamic")
+
+
+def qflash_peaks_mfma_i8(workgroups: int, iters: int, out, stream: Optional[int] = None) -> float:
+    """Enqueue the int8 matrix-rate kernel; ``out``: uint8/int64 CUDA tensor of at least
+    16 * workgroups + 16 bytes.  Returns the number of int8 operations the launch executes."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(out.device).cuda_stream
+    rc = load_library().qflash_peaks_mfma_i8(int(workgroups), int(iters), _ptr(out),
+                                             int(out.numel() * out.element_size()), ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError("qflash_peaks_mfma_i8 failed: %d" % rc)
+    return float(load_library().qflash_peaks_mfma_i8_ops(int(workgroups), int(iters)))
+
+
+def qflash_peaks_copy(src, dst, stream: Optional[int] = None) -> None:
+    """Enqueue the device-to-device copy kernel over two CUDA tensors of equal byte size."""
+    import torch
+    n = int(src.numel() * src.element_size())
+    if n != int(dst.numel() * dst.element_size()):
+        raise ValueError("src and dst must have the same size")
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device).cuda_stream
+    rc = load_library().qflash_peaks_copy(_ptr(src), _ptr(dst), n, ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError("qflash_peaks_copy failed: %d" % rc)
 
 
 class Context:

@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 import paper_2604_25306_amd as qf
-from paper_2604_25306_amd.binding import EXPORTS, QFlashParams
+from paper_2604_25306_amd.binding import EXPORTS, PEAKS_EXPORTS, QFlashParams
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -28,6 +28,12 @@ def test_header_symbols_are_exported(lib):
         header = f.read()
     declared = set(re.findall(r"\b(qflash_[a-z_]+)\s*\(", header))
     assert declared == set(EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    # the measurement kernels of the benchmark have a header of their own
+    with open(os.path.join(ROOT, "include", "qflash_peaks.h")) as f:
+        declared = set(re.findall(r"\b(qflash_peaks_[a-z0-9_]+)\s*\(", f.read()))
+    assert declared == set(PEAKS_EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
 
