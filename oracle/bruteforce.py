@@ -71,6 +71,33 @@ def fullrow_int_attention(Q, K, V, p: OracleParams, bias=None, return_state=Fals
     return out
 
 
+def fullrow_int_attention_qmax(Q, K, V, p: OracleParams, bias=None, return_state=False):
+    """The whole-row definition of the quantised-maximum variant (not the paper's): the reference
+    level is the row maximum (never below the initial maximum -2^21) rounded up to a whole number
+    of octaves, L = ceil(max * 2^k / s_inv); weights are Algorithm 2 (from the quotient step on)
+    and Eq. 10 applied to S * 2^k - L * s_inv; out = clamp(floor(P V / sum P))."""
+    S, excl = _scores(Q, K, bias)
+    Sm = np.where(excl, np.int64(-(1 << 21)), S)
+    m = np.maximum(Sm.max(axis=-1, keepdims=True), -(1 << 21))
+    s_inv = np.int64(p.s_inv)
+    L = -np.floor_divide(-(m << p.x_shift), s_inv)
+    xs = np.minimum((S << p.x_shift) - L * s_inv, 0)
+    q = _asr(xs * np.int64(p.exp_mul), p.exp_shift)
+    y = np.where(q > 31, 0, _asr(_asr(xs + q * s_inv, 1) + s_inv, np.minimum(q, 62)))
+    P = np.where(excl, 0, requant_np(y, p))
+    l = P.sum(axis=-1, keepdims=True)
+    acc = np.einsum("bhic,bhcd->bhid", P, V.astype(np.int64))
+    safe_l = np.where(l == 0, 1, l)
+    if p.out_round:
+        out = np.floor_divide(2 * acc + safe_l, 2 * safe_l)
+    else:
+        out = np.floor_divide(acc, safe_l)
+    out = np.where(l == 0, 0, np.clip(out, -128, 127)).astype(np.int8)
+    if return_state:
+        return out, {"O_acc": acc, "l": l[..., 0], "m": L[..., 0], "P": P}
+    return out
+
+
 def float_attention_ratio(Q, K, V, sQ, sK, bias_real=None, excluded=None):
     """softmax(Q K^T sQ sK / sqrt(d) [+ bias]) V in float64, in units of s_V (not rounded)."""
     d = Q.shape[-1]
@@ -91,5 +118,5 @@ def float_attention(Q, K, V, sQ, sK, sV, bias_real=None, excluded=None):
     return float_attention_ratio(Q, K, V, sQ, sK, bias_real, excluded) * sV
 
 
-__all__ = ["shift_exp2_np", "requant_np", "fullrow_int_attention", "float_attention",
+__all__ = ["shift_exp2_np", "requant_np", "fullrow_int_attention", "fullrow_int_attention_qmax", "float_attention",
            "float_attention_ratio", "score_scale"]

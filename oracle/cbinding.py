@@ -54,6 +54,13 @@ def _load():
                                                 pp, vp, vp, vp, vp, ci]
         lib.oracle_qflash_attention_per_head.restype = ci
         lib.oracle_qflash_attention_per_head.argtypes = lib.oracle_qflash_attention.argtypes
+        for name in ("oracle_qflash_attention_qmax", "oracle_qflash_attention_qmax_per_head"):
+            getattr(lib, name).restype = ci
+            getattr(lib, name).argtypes = lib.oracle_qflash_attention.argtypes
+        lib.oracle_qmax_level.restype = i64
+        lib.oracle_qmax_level.argtypes = [i64, pp]
+        lib.oracle_shift_exp2_scaled.restype = i64
+        lib.oracle_shift_exp2_scaled.argtypes = [i64, pp]
         _lib = lib
     return _lib
 
@@ -82,12 +89,32 @@ def scale_release(acc: int, a16: int) -> int:
     return int(_load().oracle_scale_release(int(acc), int(a16)))
 
 
+def qmax_level(t: int, p: OracleParams) -> int:
+    """Quantised-maximum variant (not the paper's): smallest L with L * s_inv >= t * 2^k."""
+    return int(_load().oracle_qmax_level(int(t), ctypes.byref(_cp(p))))
+
+
+def shift_exp2_scaled(xs: int, p: OracleParams) -> int:
+    """Algorithm 2 from the quotient step on, for an argument already multiplied by 2^k."""
+    return int(_load().oracle_shift_exp2_scaled(int(xs), ctypes.byref(_cp(p))))
+
+
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
+def qflash_attention_qmax(Q, K, V, p, kv_tile: int, bias=None, nthreads: int = 0,
+                          return_state: bool = False):
+    """The quantised-maximum variant (NOT the paper's Algorithm 1: the reference level of the
+    softmax is the maximum rounded up to a whole octave, so that the rescale of past
+    accumulators is an exact shift).  Arguments and results as qflash_attention; the state's
+    ``m`` holds the final level L of each row (reference = L * s_inv in scaled-score units)."""
+    return qflash_attention(Q, K, V, p, kv_tile, bias=bias, nthreads=nthreads,
+                            return_state=return_state, _variant="_qmax")
+
+
 def qflash_attention(Q, K, V, p, kv_tile: int, bias=None, nthreads: int = 0,
-                     return_state: bool = False):
+                     return_state: bool = False, _variant: str = ""):
     """Algorithm 1 on int8 arrays of shape [B,H,N,d]; returns int8 [B,H,N,d].
 
     ``p``: one OracleParams (per-tensor scales) or a sequence of H of them (per-head scales).
@@ -113,12 +140,12 @@ def qflash_attention(Q, K, V, p, kv_tile: int, bias=None, nthreads: int = 0,
     m = np.zeros((B, H, N), dtype=np.int64) if return_state else None
     viol = np.zeros(1, dtype=np.int64)
     if isinstance(p, OracleParams):
-        fn, cparams = _load().oracle_qflash_attention, _cp(p)
+        fn, cparams = getattr(_load(), "oracle_qflash_attention" + _variant), _cp(p)
     else:
         p = list(p)
         if len(p) != H:
             raise ValueError("per-head constants: need one OracleParams per head")
-        fn, cparams = _load().oracle_qflash_attention_per_head, (_CParams * H)(*[_cp(x) for x in p])
+        fn, cparams = getattr(_load(), "oracle_qflash_attention%s_per_head" % _variant), (_CParams * H)(*[_cp(x) for x in p])
     rc = fn(
         Q.ctypes.data, K.ctypes.data, V.ctypes.data, O.ctypes.data, bias_ptr, bias_B, bias_H,
         B, H, N, d, int(kv_tile), ctypes.cast(ctypes.byref(cparams), ctypes.POINTER(_CParams)),

@@ -276,6 +276,209 @@ int oracle_qflash_attention_per_head(const int8_t *Q, const int8_t *K, const int
                           O_acc, l_out, m_out, violations, nthreads);
 }
 
+/*
+ * ---------------------------------------------------------------------------
+ * NOT THE PAPER'S ALGORITHM 1: the "quantised maximum" variant.
+ *
+ * Algorithm 1 rescales the running numerator and denominator by
+ * alpha = 2^((m_old - m_new) s), an arbitrary factor in (0, 1], through
+ * ScaleRelease (Appendix B.1).  This variant keeps, instead of the running
+ * maximum itself, the smallest whole number of octaves at or above it: with
+ * one octave = s_inv units of the scaled score x' = x 2^k (Algorithm 2),
+ *
+ *     level(t) = ceil(t 2^k / s_inv),      L_new = max(L_old, level(rowmax)),
+ *
+ * and every score is referred to L_new s_inv instead of to the maximum:
+ * x' = S 2^k - L_new s_inv <= 0 goes through the remaining steps of
+ * Algorithm 2 and through Eq. 10 unchanged.  The reference level only moves
+ * by whole octaves, n = L_new - L_old >= 0, so alpha = 2^-n exactly and
+ * ScaleRelease is the arithmetic shift X <- X >> n (floor), for numerator and
+ * denominator alike.  Everything else (steps 1, 5-9, 11, bias, exclusion,
+ * initial maximum -2^21, output rule) is as in Algorithm 1.
+ *
+ * What it costs: the largest weight of a row is 127 2^-f with f in [0, 1)
+ * instead of 127, i.e. up to one bit of the 7-bit weights.  What it buys:
+ * no multiplication in the rescale, and tiles that leave the level alone
+ * (most of them) need no rescale at all.
+ *
+ * Pins (tests without a GPU): single tile == brute force over the whole row
+ * with the same reference level; level invariants (multiple of s_inv,
+ * at or above the maximum, less than one octave above it); exact
+ * re-composition of 2..10 tiles from the state after each tile with plain
+ * shifts; independence of the tiling when the level is settled in the first
+ * tile; exact invariance under adding a whole number of octaves to every
+ * score; uniform scores = floor(mean V); exclusion = deleted key; cosine
+ * against float64 softmax on tiny inputs.
+ */
+
+/* ceil(a / b) for b > 0 and any sign of a. */
+static int64_t ceil_div(int64_t a, int64_t b)
+{
+    return -floor_div(-a, b);
+}
+
+/* level(t): the smallest L with L * s_inv >= t * 2^k. */
+int64_t oracle_qmax_level(int64_t t, const oracle_params *p)
+{
+    return ceil_div(t * ((int64_t)1 << p->x_shift), (int64_t)p->s_inv);
+}
+
+/* Algorithm 2 from its quotient step on, for an argument xs <= 0 that is
+ * already in units of the scaled score (x 2^k): quotient by multiply and
+ * shift, unclamped remainder, linear fraction, shift; 0 when q > 31. */
+int64_t oracle_shift_exp2_scaled(int64_t xs, const oracle_params *p)
+{
+    int64_t q = asr(xs * (int64_t)p->exp_mul, p->exp_shift);
+    int64_t r = xs + q * (int64_t)p->s_inv;
+    if (q > 31) return 0;
+    return asr(asr(r, 1) + (int64_t)p->s_inv, (int)q);
+}
+
+/* X >> n for n >= 0 of any size (floor(X / 2^n)). */
+static int64_t shift_release(int64_t x, int64_t n)
+{
+    return asr(x, n > 62 ? 62 : (int)n);
+}
+
+/* Arguments as oracle_qflash_attention; m_out receives the final LEVEL L of every row
+ * (the reference is L * s_inv in units of the scaled score). */
+static int attention_qmax_impl(const int8_t *Q, const int8_t *K, const int8_t *V,
+                               int8_t *O, const int32_t *bias, int bias_B, int bias_H,
+                               int B, int H, int N, int d, int kv_tile,
+                               const oracle_params *p_all, int p_per_head,
+                               int64_t *O_acc, int64_t *l_out, int64_t *m_out,
+                               int64_t *violations, int nthreads)
+{
+    if (!Q || !K || !V || !O || !p_all) return -1;
+    if (B < 1 || H < 1 || N < 1 || d < 1 || kv_tile < 1) return -1;
+    if (bias && (bias_B < 1 || bias_H < 1)) return -1;
+
+    const int Tc = (N + kv_tile - 1) / kv_tile;
+    int64_t bad_total = 0;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#else
+    (void)nthreads;
+#endif
+
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad_total)
+    for (int bh = 0; bh < B * H; ++bh) {
+        const int b = bh / H, h = bh % H;
+        const oracle_params *p = p_per_head ? p_all + h : p_all;
+        const int8_t *Qh = Q + (size_t)bh * N * d;
+        const int8_t *Kh = K + (size_t)bh * N * d;
+        const int8_t *Vh = V + (size_t)bh * N * d;
+        int8_t *Oh = O + (size_t)bh * N * d;
+        const int32_t *bias_h =
+            bias ? bias + ((size_t)(b % bias_B) * bias_H + (size_t)(h % bias_H)) * N * N : NULL;
+
+        int64_t *S = (int64_t *)malloc(sizeof(int64_t) * (size_t)kv_tile);
+        int64_t *P = (int64_t *)malloc(sizeof(int64_t) * (size_t)kv_tile);
+        char *excl = (char *)malloc((size_t)kv_tile);
+        int64_t *acc = (int64_t *)malloc(sizeof(int64_t) * (size_t)d);
+        int64_t bad = 0;
+        const int64_t two_k = (int64_t)1 << p->x_shift;
+
+        for (int i = 0; i < N; ++i) {
+            for (int t = 0; t < d; ++t) acc[t] = 0;
+            int64_t l = 0;
+            int64_t L = oracle_qmax_level(M_INIT, p);      /* level of the initial maximum */
+
+            for (int j = 0; j < Tc; ++j) {
+                const int c0 = j * kv_tile;
+                const int nc = (c0 + kv_tile <= N) ? kv_tile : N - c0;
+
+                /* step 1 as in Algorithm 1 */
+                for (int c = 0; c < nc; ++c) {
+                    int64_t s = 0;
+                    for (int t = 0; t < d; ++t)
+                        s += (int64_t)Qh[(size_t)i * d + t] * (int64_t)Kh[(size_t)(c0 + c) * d + t];
+                    excl[c] = 0;
+                    if (bias_h) {
+                        int32_t bv = bias_h[(size_t)i * N + (c0 + c)];
+                        if (bv == EXCLUDED) excl[c] = 1;
+                        else s += (int64_t)bv;
+                    }
+                    S[c] = s;
+                    if (!excl[c] && !fits32(s)) bad++;
+                }
+
+                /* the tile's maximum decides the new level */
+                int64_t L_new = L;
+                for (int c = 0; c < nc; ++c) {
+                    if (excl[c]) continue;
+                    int64_t Lc = oracle_qmax_level(S[c], p);
+                    if (Lc > L_new) L_new = Lc;
+                }
+                const int64_t n = L_new - L;               /* alpha = 2^-n */
+                const int64_t ref = L_new * (int64_t)p->s_inv;
+
+                int64_t rowsum = 0;
+                for (int c = 0; c < nc; ++c) {
+                    if (excl[c]) { P[c] = 0; continue; }
+                    int64_t xs = S[c] * two_k - ref;       /* <= 0, > -s_inv for the maximum */
+                    if (xs > 0) bad++;
+                    int64_t y = oracle_shift_exp2_scaled(xs, p);
+                    if (y < 0 || !fits32(y * (int64_t)p->p_mul)) bad++;
+                    P[c] = oracle_requant(y, p);
+                    if (P[c] < 0) bad++;
+                    rowsum += P[c];
+                }
+
+                l = shift_release(l, n) + rowsum;
+                if (!fits32(l)) bad++;
+                for (int t = 0; t < d; ++t) {
+                    int64_t pv = 0;
+                    for (int c = 0; c < nc; ++c)
+                        pv += P[c] * (int64_t)Vh[(size_t)(c0 + c) * d + t];
+                    acc[t] = shift_release(acc[t], n) + pv;
+                    if (!fits32(acc[t])) bad++;
+                }
+                L = L_new;
+            }
+
+            for (int t = 0; t < d; ++t) {
+                int64_t o;
+                if (l == 0) o = 0;
+                else if (p->out_round) o = floor_div(2 * acc[t] + l, 2 * l);
+                else o = floor_div(acc[t], l);
+                if (o < -128) o = -128;
+                if (o > 127) o = 127;
+                Oh[(size_t)i * d + t] = (int8_t)o;
+                if (O_acc) O_acc[((size_t)bh * N + i) * d + t] = acc[t];
+            }
+            if (l_out) l_out[(size_t)bh * N + i] = l;
+            if (m_out) m_out[(size_t)bh * N + i] = L;
+        }
+        free(S); free(P); free(excl); free(acc);
+        bad_total += bad;
+    }
+    if (violations) *violations = bad_total;
+    return 0;
+}
+
+int oracle_qflash_attention_qmax(const int8_t *Q, const int8_t *K, const int8_t *V,
+                                 int8_t *O, const int32_t *bias, int bias_B, int bias_H,
+                                 int B, int H, int N, int d, int kv_tile,
+                                 const oracle_params *p,
+                                 int64_t *O_acc, int64_t *l_out, int64_t *m_out,
+                                 int64_t *violations, int nthreads)
+{
+    return attention_qmax_impl(Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, 0,
+                               O_acc, l_out, m_out, violations, nthreads);
+}
+
+int oracle_qflash_attention_qmax_per_head(const int8_t *Q, const int8_t *K, const int8_t *V,
+                                          int8_t *O, const int32_t *bias, int bias_B, int bias_H,
+                                          int B, int H, int N, int d, int kv_tile,
+                                          const oracle_params *p /* H entries */,
+                                          int64_t *O_acc, int64_t *l_out, int64_t *m_out,
+                                          int64_t *violations, int nthreads)
+{
+    return attention_qmax_impl(Q, K, V, O, bias, bias_B, bias_H, B, H, N, d, kv_tile, p, 1,
+                               O_acc, l_out, m_out, violations, nthreads);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP
