@@ -94,6 +94,8 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
     ctx = qf.Context(0)
     if args.no_table:
         ctx.configure(qf.CFG_EXP_TABLE, 0)
+    if args.quantised_max:
+        ctx.configure(qf.CFG_QUANTISED_MAX, 1)
     # The bias of a windowed layer is a constant of the layer: packed once, outside the timed region.
     packed = ctx.pack_bias(bias) if bias is not None and not args.plain_bias else None
     if packed is not None:
@@ -166,7 +168,7 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
 
     key = "%s/kv%d%s" % (name, tile, "/dynamic" if args.dynamic else "/per_head" if args.per_head else
                          "/plain_bias" if bias is not None and packed is None else "")
-    cnt = stored_counters(key) if batch is None and not args.no_table else None
+    cnt = stored_counters(key) if batch is None and not args.no_table and not args.quantised_max else None
     traffic = cnt.get("hbm_bytes") if cnt else None
 
     def roof(bound, achieved, peak, unit, **extra):
@@ -182,6 +184,7 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
                    "bias": None if wl.bias is None else "packed" if packed is not None else "plain",
                    "scales": "dynamic" if args.dynamic else "per_head" if args.per_head else "per_tensor",
                    "weights": "arithmetic" if args.no_table else "table where it fits",
+                   "algorithm": "quantised-maximum variant (not the paper's)" if args.quantised_max else "Algorithm 1",
                    "input_sets_rotated": len(sets), "launch": "hip_graph" if use_graph else "eager"},
         "kernel_us_events": kern_s * 1e6,
         "hot_cache": {"kernel_us_events": ev_hot / steps * 1e6, "tops": ops / (ev_hot / steps) / 1e12},
@@ -218,7 +221,8 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
         budget = 3.0 if cpu_baseline == "full" else 0.0          # "check": a single pass, for the comparison only
         while not args.dynamic and (reps == 0 or (t_cpu < budget and reps < 20)):
             t0 = time.perf_counter()
-            ref = oracle.qflash_attention(wl.Q, wl.K, wl.V, po, tile, bias=wl.bias)
+            ref = (oracle.qflash_attention_qmax if args.quantised_max else oracle.qflash_attention)(
+                wl.Q, wl.K, wl.V, po, tile, bias=wl.bias)
             t_cpu += time.perf_counter() - t0
             reps += 1
         same = bool(np.array_equal(ref, sets[0][3].cpu().numpy()))
@@ -295,6 +299,9 @@ def main():
     ap.add_argument("--no-table", action="store_true",
                     help="evaluate the weight of every score arithmetically (Algorithm 2 in the vector ALUs) "
                          "instead of reading it from the table in LDS; same bits")
+    ap.add_argument("--quantised-max", action="store_true",
+                    help="time the quantised-maximum variant (QFLASH_CFG_QUANTISED_MAX: NOT the paper's "
+                         "Algorithm 1, different results; checked against its own oracle)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device-to-device copy, so that a rocprofv3 --pmc "
                          "trace of this command holds a kernel of known HBM traffic")
@@ -347,7 +354,7 @@ def main():
 
     # The other benchmark configurations, timed the same way with fewer steps, each checked against
     # the oracle (one pass) unless the baseline is switched off.
-    if not args.no_others and args.workload is None and args.batch is None and not (args.dynamic or args.per_head):
+    if not args.no_others and args.workload is None and args.batch is None and not (args.dynamic or args.per_head or args.quantised_max):
         others = {}
         for wname in BASELINE_CONFIGS:
             for tile in CONFIGS[wname][4]:

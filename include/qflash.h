@@ -83,9 +83,21 @@ int qflash_create(qflash_ctx** out, int device_id);
  * read the old table.  A call on a stream that is being captured into a HIP graph builds nothing:
  * it uses a table only if an earlier call on that stream has built it (such a table is then kept
  * for good, because the graph reads it on every replay) and computes arithmetically otherwise.
+ *
+ * QFLASH_CFG_QUANTISED_MAX (default 0).  1 switches the context to a variant that is NOT the
+ * paper's Algorithm 1 and gives different (slightly less accurate) results; never on by default.
+ * Instead of the running maximum it keeps the maximum rounded up to a whole octave (a multiple of
+ * s_inv score units) as the reference of the integer softmax; the reference then only moves by
+ * whole octaves, the max-offset factor alpha of Algorithm 1 (step 4) is an exact power of two, and
+ * ScaleRelease (Appendix B.1) is an arithmetic shift of numerator and denominator, skipped for
+ * tiles that move no reference.  The largest weight of a row is 127 * 2^-f, 0 <= f < 1, instead of
+ * 127.  Everything else (Algorithm 2, Eq. 10, bias, exclusion, normalisation, output scale) is
+ * unchanged.  Requires x_shift == 0 in every qflash_params of the call (PARAM otherwise); not
+ * available through qflash_attention_static and qflash_attention_dynamic (PARAM).
  * Errors: NULL, CTX, PARAM (unknown key or value).
  */
 #define QFLASH_CFG_EXP_TABLE 1
+#define QFLASH_CFG_QUANTISED_MAX 2
 int qflash_configure(qflash_ctx* ctx, int key, int value);
 
 /*

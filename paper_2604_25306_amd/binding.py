@@ -26,6 +26,7 @@ PEAKS_EXPORTS = ["qflash_peaks_mfma_i8", "qflash_peaks_mfma_i8_ops", "qflash_pea
 MAX_PARAM_HEADS = 64
 
 CFG_EXP_TABLE = 1
+CFG_QUANTISED_MAX = 2     # a variant that is not the paper's Algorithm 1 (see qflash.h)
 
 
 class QFlashError(RuntimeError):

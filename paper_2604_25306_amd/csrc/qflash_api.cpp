@@ -44,6 +44,7 @@ struct qflash_ctx {
     int lds_limit;        // LDS bytes one workgroup may allocate on this device
     int n_cu;             // compute units
     int use_table;        // QFLASH_CFG_EXP_TABLE
+    int qmax;             // QFLASH_CFG_QUANTISED_MAX
     uint8_t* tables;      // device, kTableSlots x kTableMaxBytes
     uint8_t* scratch_ptr; // device address of `scratch` on this context's GPU, or nullptr
     int n_slots;          // slots in use
@@ -100,6 +101,7 @@ extern "C" int qflash_create(qflash_ctx** out, int device_id) {
     c->lds_limit = lds;
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     c->use_table = 1;
+    c->qmax = 0;
     c->n_slots = 0;
     c->tables = nullptr;
     c->launches = 0;
@@ -155,9 +157,10 @@ extern "C" int qflash_configure(qflash_ctx* ctx, int key, int value) {
         std::lock_guard<std::mutex> lk(g_mu);
         if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
     }
-    if (key != QFLASH_CFG_EXP_TABLE || (value != 0 && value != 1)) return QFLASH_ERR_PARAM;
+    if ((key != QFLASH_CFG_EXP_TABLE && key != QFLASH_CFG_QUANTISED_MAX) || (value != 0 && value != 1)) return QFLASH_ERR_PARAM;
     std::lock_guard<std::mutex> lk(ctx->mu);
-    ctx->use_table = value;
+    if (key == QFLASH_CFG_EXP_TABLE) ctx->use_table = value;
+    else ctx->qmax = value;
     return QFLASH_OK;
 }
 
@@ -185,7 +188,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit, n_cu;
     uint8_t* scratch_ptr;
-    bool table_wanted;
+    bool table_wanted, qmax;
     {
         std::lock_guard<std::mutex> lk(g_mu);
         if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
@@ -197,7 +200,10 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     {
         std::lock_guard<std::mutex> lk(ctx->mu);
         table_wanted = ctx->use_table != 0;
+        qmax = ctx->qmax != 0;
     }
+    // The quantised-maximum variant takes its constants from the host and needs x_shift = 0.
+    if (qmax && (hc_dev || static_table)) return QFLASH_ERR_PARAM;
     if (!Q || !K || !V || !O || (!p && !hc_dev)) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
     if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
@@ -215,6 +221,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     for (int h = 0; h < n_p; ++h) {
         if (!qflash_params_ok(p[h])) return QFLASH_ERR_PARAM;
         if (p[h].out_round != p[0].out_round) return QFLASH_ERR_PARAM;   // one rounding mode per call
+        if (qmax && p[h].x_shift != 0) return QFLASH_ERR_PARAM;
     }
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
     if (bias && ((uintptr_t)bias & (bias_packed ? 15u : 3u))) return QFLASH_ERR_ALIGN;
@@ -239,6 +246,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.B = B; a.H = H; a.N = N;
     a.out_round = hc_dev ? out_round_dev : p[0].out_round;
     a.per_head = per_head ? 1 : 0;
+    a.qmax = qmax ? 1 : 0;
     a.hc_dev = hc_dev;
     a.n_cu = n_cu;
 #ifdef QF_TRACE
@@ -265,7 +273,8 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
             if (x_p + 16 <= kTableMaxBytes) table_hint = ((int)x_p + 1 + 15) & ~15;
         }
         // a table only pays while it is smaller than the Q, K, V, O bytes of the workgroup
-        if (!qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, table_hint, &a) && table_hint > 0)
+        if (qmax) a.cu_mode = 0;          // the whole-compute-unit kernel exists for Algorithm 1 only
+        else if (!qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, table_hint, &a) && table_hint > 0)
             qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, 0, &a);
     }
     // wave priority by dispatch round: only for launches of two to four rounds (0 = off)
@@ -439,11 +448,16 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
                                  int bias_H, qflash_plan_info* out) {
     if (!out) return QFLASH_ERR_NULL;
     int lds_limit = 160 * 1024, n_cu = 256;
+    bool qmax = false;
     if (ctx) {
-        std::lock_guard<std::mutex> lk(g_mu);
-        if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
-        lds_limit = ctx->lds_limit;
-        n_cu = ctx->n_cu;
+        {
+            std::lock_guard<std::mutex> lk(g_mu);
+            if (live_contexts().find(ctx) == live_contexts().end()) return QFLASH_ERR_CTX;
+            lds_limit = ctx->lds_limit;
+            n_cu = ctx->n_cu;
+        }
+        std::lock_guard<std::mutex> lk(ctx->mu);
+        qmax = ctx->qmax != 0;
     }
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
     if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
@@ -461,7 +475,7 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
     a.n_cu = n_cu;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
     std::memset(out, 0, sizeof *out);
-    if (qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, kPlanQueryTableBytes, &a)) {
+    if (!qmax && qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, kPlanQueryTableBytes, &a)) {
         out->kernel = 3;
         out->pairs_per_workgroup = a.cu_heads;
         out->wavefronts_per_pair = a.cu_waves;

@@ -55,6 +55,7 @@ struct QflashKernelArgs {
 #ifdef QF_TRACE
     unsigned long long* trace;   // instrumented builds only: [workgroup][wavefront][16] timestamps
 #endif
+    int qmax;                // 1: the quantised-maximum variant (not Algorithm 1 as printed; every x_shift must be 0)
     int per_head;            // 0: hc[0] serves every head; 1: head h uses hc[h] (H <= kQflashMaxParamHeads)
     // Constants computed on the GPU (dynamic quantisation): if set, the kernel reads this device
     // structure instead of hc[]; exp_mode is then 0 (the host does not know the constants).
@@ -82,6 +83,8 @@ QF_UNIT_HD inline int qflash_unit_of_workgroup(int wg, int units_per_xcd, int xc
 
 // Enqueue the forward kernel for head size d (32|64), KV tile (64|128).  Returns a hipError_t value.
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
+// The same kernels instantiated for the quantised-maximum variant (called by qflash_launch_fwd when args.qmax).
+int qflash_launch_fwd_qmax(const QflashKernelArgs& args, int d, int kv_tile, size_t lds_bytes, int lds_limit, int threads, void* stream);
 
 // Choose the kernel variant for BH heads of N rows and fill the work decomposition fields
 // (resident, pipelined, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd, xcd_period, same_head; reads bias, bias_B, B, H, per_head).

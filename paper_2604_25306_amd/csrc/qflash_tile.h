@@ -110,6 +110,14 @@ __device__ __forceinline__ unsigned recip_ceil(unsigned d) {
     return q + 1;
 }
 
+// Quantised-maximum variant: the reference level the initial maximum -2^21 rounds up to,
+// ceil(-2^21 / s_inv) * s_inv = -floor(2^21 / s_inv) * s_inv (a_mul = ceil(2^30 / s_inv)).
+__device__ __forceinline__ int qmax_initial_reference(int s_inv, int a_mul) {
+    unsigned q = __umulhi(1u << 23, (unsigned)a_mul);
+    if (q * (unsigned)s_inv > (1u << 21)) q -= 1;
+    return -(int)(q * (unsigned)s_inv);
+}
+
 // ---------------------------------------------------------------------- per-wavefront state
 
 template <int D>
@@ -121,11 +129,14 @@ struct RowState {
 
 // One KV tile for one wavefront.  sK: K rows of the tile (row pitch KROW), sV: V^T with the tile's
 // columns starting at column 0 (row pitch VROW).  n_valid = number of real kv rows in the tile.
+// QMAX selects the quantised-maximum variant, which is NOT Algorithm 1 as printed: RowState::m is
+// then the reference level (the running maximum rounded up to a multiple of s_inv; x_shift must be
+// 0), scores are referred to it, and ScaleRelease is an exact shift.
 // XM selects how the int8 weight of a score is obtained: kExpShift (Algorithm 2 + Eq. 10 in the
 // ALUs, any x_shift), kExpShift0 (the same, x_shift == 0) or kExpTable (one LDS look-up in a table
 // of the same function, see qflash_build_table).
 //
-// Offsets.  Numerator accumulators always carry +2^31 (see ReleaseConst).  In table mode without
+// Offsets.  Numerator accumulators always carry +2^30 (see ReleaseConst).  In table mode without
 // bias the scores can carry it too (SB): the first MFMA of a score block starts from a
 // block of the offset instead of zeros, which costs nothing, and then
 //   table index = max(0, s - m + x_p) = (s + 2^30) -sat- (m + 2^30 - x_p)
@@ -181,7 +192,7 @@ __device__ __forceinline__ SwizzledLane swizzled_lane_offsets(int lane) {
 
 // NG: 0, or the number of groups of 8 keys the (ragged) tile has, known at compile time: the tests
 // "does this group exist" then cost nothing; n_valid_rt still tells which keys of the last group exist.
-template <int D, int BC, int BIAS, int XM, bool SB, bool FULL, bool FIRST, int LAY = kLayPadded, int NG = 0>
+template <int D, int BC, int BIAS, int XM, bool SB, bool FULL, bool FIRST, int LAY = kLayPadded, int NG = 0, bool QMAX = false>
 __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, const int8_t* sK, int KROW,
                                             const int8_t* sV, int VROW, int n_valid_rt, int x_p,
                                             const int32_t* bias_row /* + c0 */,
@@ -280,14 +291,48 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         const HalfPair hp = both_halves(m_new);
         m_new = smax<SB>(hp.x, hp.y);
     }
+    // ---- QMAX (not Algorithm 1): the reference moves up by whole octaves only.  st.m is the old
+    //      reference (a multiple of s_inv, x_shift = 0) and m_new so far the larger of it and the
+    //      tile's maximum; n = ceil((m_new - st.m) / s_inv) octaves are added.  The quotient by
+    //      multiply-high with ceil(2^30 / s_inv) overshoots by at most one (numerator < 2^24),
+    //      which one comparison corrects.
+    int n_oct = 0;
+    if (QMAX) {
+        const unsigned x = ((unsigned)m_new - (unsigned)st.m) + (unsigned)(c.s_inv - 1);
+        unsigned q = __umulhi(x << 2, (unsigned)a_mul);
+        if (q * (unsigned)c.s_inv > x) q -= 1;
+        n_oct = (int)q;
+        m_new = st.m + n_oct * c.s_inv;
+    }
     const int lo = m_new + c.x_floor;
     const int m2 = m_new - 2 * c.s_inv;
     // ---- step 4: max-offset factor alpha, brought to 16 fractional bits
     ReleaseConst rel;
-    if (!FIRST) {
+    if (!FIRST && !QMAX) {
         const int a_hat = shift_exp2<KZ>(smax<SB>(st.m, lo), m_new, m2, c);
         rel = make_release(min(((unsigned)a_hat * (unsigned)a_mul) >> 14, 65536u));
     }
+    // ---- steps 9,10 (the part that concerns the past): ScaleRelease of denominator and numerator.
+    //      QMAX: alpha = 2^-n, an arithmetic shift; on the offset representation
+    //      floor(x / 2^n) + 2^30 = ((x + 2^30) >> n) + (2^30 - (2^30 >> n)) for n <= 30, and n = 30
+    //      stands for every larger n (|x| < 2^26).
+    auto release_past = [&]() {
+        if (QMAX) {
+            const int n = min(n_oct, 30);
+            const unsigned addc = (unsigned)kAccBias - ((unsigned)kAccBias >> n);
+            st.l = st.l >> n;
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = (int)(((unsigned)st.acc[t][v] >> n) + addc);
+        } else {
+            st.l = release_l(st.l, rel);
+#pragma unroll
+            for (int t = 0; t < TB; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) st.acc[t][v] = release_acc(st.acc[t][v], rel);
+        }
+    };
     v4i pk[KB];
     int rowsum = 0;
     if (XM == kExpTable) {
@@ -295,7 +340,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         //      the LDS answers, then pack.  Index 0 of the table is the weight 0 of everything at
         //      or below -x_p (excluded scores included).
         const unsigned x_p_v = (unsigned)to_vgpr(x_p);
-        const unsigned edge = (unsigned)m_new - x_p_v;       // score_biased: m + 2^31 - x_p > 0
+        const unsigned edge = (unsigned)m_new - x_p_v;       // score_biased: m + 2^30 - x_p > 0
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -312,13 +357,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                     }
                 }
         __builtin_amdgcn_sched_barrier(0);
-        if (!FIRST) {
-            st.l = release_l(st.l, rel);
-#pragma unroll
-            for (int t = 0; t < TB; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) st.acc[t][v] = release_acc(st.acc[t][v], rel);
-        }
+        if (!FIRST) release_past();
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
@@ -367,15 +406,12 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         if (FIRST) {
             st.l = rowsum;
         } else {
-            st.l = release_l(st.l, rel) + rowsum;
-#pragma unroll
-            for (int t = 0; t < TB; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) st.acc[t][v] = release_acc(st.acc[t][v], rel);
+            release_past();
+            st.l += rowsum;
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // ---- step 8: O^T += V_j^T P^T (the first tile starts the accumulators at their offset 2^31)
+    // ---- step 8: O^T += V_j^T P^T (the first tile starts the accumulators at their offset 2^30)
 #pragma unroll
     for (int t = 0; t < TB; ++t)
 #pragma unroll
