@@ -67,15 +67,6 @@ std::set<const qflash_ctx*>& live_contexts() {
 
 }  // namespace
 
-extern "C" int qflash_params_from_scales(double sQ, double sK, double sV, int d, qflash_params* out) {
-    if (!out) return QFLASH_ERR_NULL;
-    if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
-    if (!(sQ > 0.0) || !(sK > 0.0) || !(sV > 0.0) || !std::isfinite(sQ) || !std::isfinite(sK) ||
-        !std::isfinite(sV))
-        return QFLASH_ERR_PARAM;
-    return qflash_derive_params(sQ, sK, std::sqrt((double)d), out);
-}
-
 extern "C" int qflash_create(qflash_ctx** out, int device_id) {
     if (!out) return QFLASH_ERR_NULL;
     *out = nullptr;
@@ -204,27 +195,12 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     }
     // The quantised-maximum variant takes its constants from the host and needs x_shift = 0.
     if (qmax && (hc_dev || static_table)) return QFLASH_ERR_PARAM;
-    if (!Q || !K || !V || !O || (!p && !hc_dev)) return QFLASH_ERR_NULL;
-    if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
-    if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
-    if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
-    if (per_head && H > QFLASH_MAX_PARAM_HEADS) return QFLASH_ERR_SHAPE;
-    if (bias) {
-        if (bias_B < 1 || bias_H < 1) return QFLASH_ERR_SHAPE;
-        if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
-        if (bias_packed && qflash_packed_bias_words(bias_B * bias_H, N) >= ((int64_t)1 << 29)) return QFLASH_ERR_SHAPE;
-    } else if (bias_packed) {
-        return QFLASH_ERR_NULL;
+    {
+        const int rc = qflash_check_call(Q, K, V, O, bias, bias_B, bias_H, bias_packed, B, H, N, d, kv_tile, p, per_head,
+                                         hc_dev != nullptr, qmax);
+        if (rc != QFLASH_OK) return rc;
     }
-    if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
     const int n_p = hc_dev ? 0 : per_head ? H : 1;
-    for (int h = 0; h < n_p; ++h) {
-        if (!qflash_params_ok(p[h])) return QFLASH_ERR_PARAM;
-        if (p[h].out_round != p[0].out_round) return QFLASH_ERR_PARAM;   // one rounding mode per call
-        if (qmax && p[h].x_shift != 0) return QFLASH_ERR_PARAM;
-    }
-    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u) return QFLASH_ERR_ALIGN;
-    if (bias && ((uintptr_t)bias & (bias_packed ? 15u : 3u))) return QFLASH_ERR_ALIGN;
     // The entry point that allocates nothing keeps its one weight table in the static device array:
     // constants whose table is larger than that are refused, not silently run another way.
     int static_xp = 0, static_np = 0;

@@ -307,38 +307,12 @@ int launch_cu(const QflashKernelArgs& a, size_t lds, int lds_limit, hipStream_t 
 }  // namespace
 
 // LDS bytes of the kernel above for `heads` pairs of N rows and a table of table_bytes.
-static size_t cu_lds_bytes(int N, int heads, int table_bytes) {
-    const size_t rows16 = (size_t)((N + 15) & ~15);
-    const size_t table = ((size_t)table_bytes + 1023) & ~(size_t)1023;
-    return table + (size_t)heads * 3 * rows16 * 64 + 1024 + 4 * (5 * (size_t)heads + 1)
-#ifdef QF_TRACE
-           + 8 + 2048
-#endif
-        ;
-}
-
-int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_bytes, QflashKernelArgs* a) {
-    a->cu_mode = 0;
-    if (d != 64 || kv_tile != 64 || a->bias || a->per_head || N > 256) return 0;
-    const int cus = a->n_cu > 0 ? a->n_cu : 256;
-    const int hpw = (BH + cus - 1) / cus;                 // every pair in a single round of workgroups
-    if (cu_lds_bytes(N, hpw, table_bytes) > (size_t)lds_limit) return 0;
-    const int nblk = (N + 31) / 32;
-    const int units = hpw * nblk;
-    a->cu_mode = 1;
-    a->cu_heads = hpw;
-    a->cu_groups = (BH + hpw - 1) / hpw;
-    a->cu_waves = units < 16 ? units : 16;
-    a->cu_table_lds = (table_bytes + 1023) & ~1023;
-    return 1;
-}
-
 int qflash_launch_fwd_cu(const QflashKernelArgs& a, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     if (!a.cu_mode || a.cu_heads < 1 || a.cu_waves < 1 || a.cu_waves > 16 || a.N > 256 || a.bias) return (int)hipErrorInvalidValue;
     const bool table = a.exp_mode == kExpTable || a.exp_mode == kExpAuto;
     if (table && a.lut_bytes_max > a.cu_table_lds) return (int)hipErrorInvalidValue;
-    const size_t lds = cu_lds_bytes(a.N, a.cu_heads, table ? a.cu_table_lds : 0);
+    const size_t lds = qflash_cu_lds_bytes(a.N, a.cu_heads, table ? a.cu_table_lds : 0);
     if (lds > (size_t)lds_limit) return (int)hipErrorInvalidValue;
     if (a.exp_mode == kExpAuto) return launch_cu<kExpAuto>(a, lds, lds_limit, st);
     if (a.exp_mode == kExpTable) return launch_cu<kExpTable>(a, lds, lds_limit, st);

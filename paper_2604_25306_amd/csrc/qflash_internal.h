@@ -81,6 +81,24 @@ QF_UNIT_HD inline int qflash_unit_of_workgroup(int wg, int units_per_xcd, int xc
     return (k / q) * xcd_period + x * q + k % q;
 }
 
+// Wavefronts per workgroup of the resident kernel (short sequences, N <= 256: 8, held to 128
+// registers so that two workgroups share a compute unit; longer ones: 12), and of the streamed one.
+constexpr int kResidentMaxWavesNarrow = 8;
+constexpr int kResidentMaxWavesWide = 12;
+constexpr int kStreamWaves = 4;
+constexpr int kStreamRows = kStreamWaves * 32;
+
+// Argument checks of the attention entry points (host only).  Returns QFLASH_OK or the error code.
+int qflash_check_call(const void* Q, const void* K, const void* V, const void* O, const int32_t* bias, int bias_B,
+                      int bias_H, bool bias_packed, int B, int H, int N, int d, int kv_tile, const qflash_params* p,
+                      bool per_head, bool consts_on_device, bool qmax);
+
+// LDS bytes of the resident kernel for `heads` pairs of N rows (ring_tile != 0: two KV tiles of that
+// size instead of the whole sequence) plus a weight table; 0 if that exceeds lds_limit.  LDS bytes
+// of the whole-compute-unit kernel.
+size_t qflash_resident_lds_bytes(int N, int d, int heads, int table_bytes, int lds_limit, int ring_tile = 0);
+size_t qflash_cu_lds_bytes(int N, int heads, int table_bytes);
+
 // Enqueue the forward kernel for head size d (32|64), KV tile (64|128).  Returns a hipError_t value.
 int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_limit, void* stream);
 // The same kernels instantiated for the quantised-maximum variant (called by qflash_launch_fwd when args.qmax).

@@ -67,7 +67,7 @@ extern __shared__ __align__(16) int8_t smem[];
 // 128 registers so that two workgroups share a CU.  Longer sequences get up to 12 wavefronts of
 // up to 168 registers (the 32-bit rescale and wider tiles need more live values).
 template <bool NARROW>
-constexpr int resident_max_waves() { return NARROW ? 8 : 12; }
+constexpr int resident_max_waves() { return NARROW ? kResidentMaxWavesNarrow : kResidentMaxWavesWide; }
 
 // Where this lane's bias values start.  Plain layout [bias_B,bias_H,N,N]: the lane's row (lanes
 // beyond the sequence read row 0; their results are never stored).  Packed layout
@@ -460,9 +460,7 @@ __global__ __launch_bounds__(64 * resident_max_waves<NARROW>(), (resident_min_wa
 
 // -------------------------------------------------------------------------- stream kernel
 
-constexpr int kStreamWaves = 4;
 constexpr int kStreamThreads = kStreamWaves * 64;
-constexpr int kStreamRows = kStreamWaves * 32;
 
 template <int D, int BC, int BIAS, bool QMAX>
 __global__ __launch_bounds__(kStreamThreads) void qflash_fwd_stream(const QflashKernelArgs a) {

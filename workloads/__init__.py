@@ -150,9 +150,13 @@ for _name, (_h, _n, _d, _win) in TABLE1.items():
     for _b in (1, 8):
         CONFIGS["%s_b%d" % (_name, _b)] = ((_b * max(_win, 1), _h, _n, _d), "normal", 1.0, 0.0, (64,), _win)
 CONFIG_ORDER = list(CONFIGS)
+# A shape outside the paper's workloads, for measuring the corner where a d = 32 sequence no longer
+# fits LDS and the streamed kernel takes over (appended after CONFIG_ORDER is fixed: seeds unchanged).
+CONFIGS["long_d32_n2100"] = ((8, 8, 2100, 32), "normal", 1.0, 0.0, (64, 128), False)
+CONFIG_ORDER.append("long_d32_n2100")
 HEADLINE = "vit_b16_b64"
 BASELINE_CONFIGS = CONFIG_ORDER[:5]           # the five benchmark configurations
-TABLE1_CONFIGS = CONFIG_ORDER[5:]             # Table 1 at batch 1 and 8
+TABLE1_CONFIGS = CONFIG_ORDER[5:5 + 2 * len(TABLE1)]   # Table 1 at batch 1 and 8
 
 
 def make_float_qkv(name: str, batch: Optional[int] = None):
