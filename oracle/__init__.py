@@ -37,10 +37,10 @@ from .bruteforce import (
     float_attention_ratio,
 )
 
-from .dynamic import dynamic_quantize, qflash_attention_dynamic
+from .dynamic import dynamic_quantize, qflash_attention_dynamic, dynamic_bias_to_int
 
 __all__ = [
-    "dynamic_quantize", "qflash_attention_dynamic",
+    "dynamic_quantize", "qflash_attention_dynamic", "dynamic_bias_to_int",
     "OracleParams", "derive_params", "build_oracle", "qflash_attention", "shift_exp2",
     "shift_exp2_quotient", "requant", "alpha16", "scale_release", "num_threads",
     "shift_exp2_np", "requant_np", "fullrow_int_attention", "float_attention",

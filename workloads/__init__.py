@@ -160,15 +160,38 @@ TABLE1_CONFIGS = CONFIG_ORDER[5:5 + 2 * len(TABLE1)]   # Table 1 at batch 1 and 
 
 
 def make_float_qkv(name: str, batch: Optional[int] = None):
-    """The float32 Q, K, V a non-windowed workload is quantised from (same seed, same draws):
-    input of the dynamic-quantisation path."""
+    """The float32 Q, K, V a workload is quantised from (same seed, same draws): input of the
+    dynamic-quantisation path."""
     shape, dist, sigma, ofrac, _, windowed = CONFIGS[name]
-    if windowed:
-        raise ValueError("float inputs are offered for the non-windowed workloads")
     if batch is not None:
         shape = (int(batch),) + tuple(shape[1:])
     rng = np.random.default_rng(1000 + CONFIG_ORDER.index(name) + 1)
     return tuple(_draw(rng, shape, dist, sigma, ofrac) for _ in range(3))
+
+
+def make_float_window_bias(name: str, n_windows: Optional[int] = None):
+    """Real-valued bias of a windowed workload for the dynamic-quantisation path: relative-position
+    bias (float32 [windows, heads, N, N], table ~ N(0, 0.5^2) gathered as in swin_window_bias) and
+    the shifted-window exclusion mask (uint8, same shape, 1 = excluded; odd windows carry it)."""
+    shape, _, _, _, _, windowed = CONFIGS[name]
+    if not windowed:
+        raise ValueError("not a windowed workload")
+    n_win = int(n_windows) if n_windows is not None else (64 if windowed is True else int(windowed))
+    heads, n = shape[1], shape[2]
+    win = int(round(np.sqrt(n)))
+    rng = np.random.default_rng(2000 + CONFIG_ORDER.index(name) + 1)
+    table = rng.standard_normal(size=(heads, (2 * win - 1) ** 2)) * 0.5
+    ys, xs = np.divmod(np.arange(n), win)
+    dy = ys[:, None] - ys[None, :] + (win - 1)
+    dx = xs[:, None] - xs[None, :] + (win - 1)
+    rel = table[:, dy * (2 * win - 1) + dx].astype(np.float32)
+    split = win - win // 2
+    label = (ys >= split).astype(np.int64) * 2 + (xs >= split).astype(np.int64)
+    differ = label[:, None] != label[None, :]
+    excluded = np.zeros((n_win, heads, n, n), dtype=np.uint8)
+    excluded[1::2] = differ[None, None]
+    bias_real = np.ascontiguousarray(np.broadcast_to(rel[None], (n_win, heads, n, n)))
+    return bias_real, excluded
 
 
 def head_gains(H: int) -> np.ndarray:
