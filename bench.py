@@ -80,9 +80,12 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
     bias_bytes = wl.bias.nbytes if wl.bias is not None else 0
     if args.dynamic:
         # float32 Q, K, V read twice (abs-max, quantise), int8 copies written and read, O written
-        from workloads import make_float_qkv
+        from workloads import make_float_qkv, make_float_window_bias
         floats = make_float_qkv(name, batch=batch)
         io_bytes = (2 * 12 + 3 + 3 + 1) * B * H * N * d
+        # windowed workloads: the bias arrives in real units with an exclusion mask and is converted
+        # on the GPU with the scales found on the fly (read 5 B, written and read 4 B per element)
+        dyn_bias = make_float_window_bias(name) if wl.bias is not None else None
     n_sets = max(1, -(-int(LLC_BYTES * 1.25) // io_bytes))
     src = floats if args.dynamic else (wl.Q, wl.K, wl.V)
     base = [torch.from_numpy(x).to(dev) for x in src]
@@ -101,12 +104,20 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
     if packed is not None:
         bias_bytes = packed.numel() * 4
     if args.dynamic:
-        ws = torch.empty(qf.qflash_dynamic_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=dev)
+        packed = None
+        if dyn_bias is not None:
+            dbias, dmask = (torch.from_numpy(x).to(dev) for x in dyn_bias)
+            bias_bytes = 13 * dbias.numel()
+            ws = torch.empty(qf.qflash_dynamic_bias_workspace_bytes(B, H, N, d, dbias.shape[0], dbias.shape[1]),
+                             dtype=torch.uint8, device=dev)
+        else:
+            dbias = dmask = None
+            ws = torch.empty(qf.qflash_dynamic_workspace_bytes(B, H, N, d), dtype=torch.uint8, device=dev)
 
     def step(i):
         q, k, v, o = sets[i % len(sets)]
         if args.dynamic:
-            ctx.attention_dynamic(q, k, v, o, tile, ws)
+            ctx.attention_dynamic(q, k, v, o, tile, ws, bias_real=dbias, excluded=dmask)
         elif packed is not None:
             ctx.attention_packed_bias(q, k, v, o, params_c if args.per_head else params, tile, packed,
                                       bias.shape[0], bias.shape[1])
@@ -181,7 +192,8 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
         "workload": name, "value": tops, "ms_per_step": sec_per_step * 1e3, "us_per_layer": sec_per_step * 1e6,
         "steps": steps,
         "config": {"workload": name, "B": B, "H": H, "N": N, "d": d, "kv_tile": tile,
-                   "bias": None if wl.bias is None else "packed" if packed is not None else "plain",
+                   "bias": None if wl.bias is None else "real units + mask, converted on the GPU" if args.dynamic
+                   else "packed" if packed is not None else "plain",
                    "scales": "dynamic" if args.dynamic else "per_head" if args.per_head else "per_tensor",
                    "weights": "arithmetic" if args.no_table else "table where it fits",
                    "algorithm": "quantised-maximum variant (not the paper's)" if args.quantised_max else "Algorithm 1",
@@ -207,7 +219,8 @@ def measure(qf, torch, np, args, name, steps, warmup, cpu_baseline, batch=None):
         import oracle
         if args.dynamic:
             t0 = time.perf_counter()
-            ref, _ = oracle.qflash_attention_dynamic(*floats, tile)
+            ref, _ = oracle.qflash_attention_dynamic(*floats, tile, bias_real=dyn_bias[0] if dyn_bias else None,
+                                                     excluded=dyn_bias[1] if dyn_bias else None)
             t_cpu, reps = time.perf_counter() - t0, 1
             po = None
         elif args.per_head:

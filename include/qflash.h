@@ -251,8 +251,9 @@ int qflash_attention_packed_bias(qflash_ctx* ctx,
  *               aligned, caller-owned; it holds the int8 copies of Q, K, V among other things and
  *               must stay untouched until the stream has executed the work.  The call allocates
  *               nothing.
- *   out_round, kv_tile, hip_stream  as for qflash_attention.  No bias in this entry point (an
- *               integer bias is expressed in a score unit that is only known on the GPU here).
+ *   out_round, kv_tile, hip_stream  as for qflash_attention.  No integer bias in these entry
+ *               points (it is expressed in a score unit that is only known on the GPU here);
+ *               qflash_attention_dynamic_bias takes one in real units.
  * The weight table of the look-up mode, if the constants allow one, is built on the GPU as well
  * (in the workspace).
  * Errors: CTX, NULL, SHAPE (also: workspace too small), TILE, PARAM (out_round), ALIGN, DEVICE,
@@ -273,6 +274,35 @@ int qflash_attention_dynamic(qflash_ctx* ctx,
                              qflash_dynamic_info* info /* device or NULL */,
                              void* workspace /* device */, size_t workspace_bytes,
                              void* hip_stream);
+
+/*
+ * The same with an additive bias given in real units and an exclusion mask (windowed attention:
+ * relative-position bias, shifted-window mask), for callers whose scales are only found on the fly.
+ * The paper adds the bias to S inside Algorithm 1 (step 1) and leaves its quantisation open; here
+ * the GPU brings it to the unit of the integer score with the scales it has just computed:
+ *   unit = (s_Q * s_K) / sqrt(d),   b_hat = clip(floor(double(b) / unit + 0.5), -(2^20-1), 2^20-1)
+ * in float64, one rounding per operation; excluded pairs take no part in the maximum and get
+ * weight 0 (QFLASH_EXCLUDED).  The converted bias is written to the workspace in the packed layout
+ * (see qflash_pack_bias) and the attention kernel reads it from there.
+ *
+ *   bias_real  device or NULL, float32 [bias_B,bias_H,N,N] contiguous, 4-byte aligned, finite;
+ *              NULL means a bias of zeros (mask only).
+ *   excluded   device or NULL, uint8 [bias_B,bias_H,N,N]; nonzero excludes the pair.
+ *              At least one of the two must be given (NULL otherwise); indexing as for qflash_attention.
+ *   workspace  at least qflash_dynamic_bias_workspace_bytes(B,H,N,d,bias_B,bias_H) bytes (0: the
+ *              extents are not supported).
+ * Everything else, and the errors, as qflash_attention_dynamic; SHAPE also for bias extents.
+ */
+size_t qflash_dynamic_bias_workspace_bytes(int B, int H, int N, int d, int bias_B, int bias_H);
+
+int qflash_attention_dynamic_bias(qflash_ctx* ctx,
+                                  const float* Qf, const float* Kf, const float* Vf, int8_t* O,
+                                  const float* bias_real /* device or NULL */,
+                                  const uint8_t* excluded /* device or NULL */, int bias_B, int bias_H,
+                                  int B, int H, int N, int d, int kv_tile, int out_round,
+                                  qflash_dynamic_info* info /* device or NULL */,
+                                  void* workspace /* device */, size_t workspace_bytes,
+                                  void* hip_stream);
 
 /*
  * How a call would be laid out on the GPU (host only; nothing is enqueued and no GPU is touched

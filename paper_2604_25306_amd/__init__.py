@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     qflash_params_from_scales, qflash_create, qflash_configure, qflash_attention,
     qflash_attention_static,
     qflash_attention_per_head, qflash_dynamic_workspace_bytes, qflash_attention_dynamic, DynamicInfo,
+    qflash_dynamic_bias_workspace_bytes,
     qflash_destroy, qflash_strerror, EXCLUDED, ERR, CFG_EXP_TABLE, CFG_QUANTISED_MAX,
     MAX_PARAM_HEADS, qflash_packed_bias_bytes, qflash_pack_bias, qflash_attention_packed_bias,
     params_array, PlanInfo, qflash_plan_query, qflash_plan_unit, CacheInfo, qflash_cache_query,

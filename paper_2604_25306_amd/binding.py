@@ -17,6 +17,7 @@ ERR = {"OK": 0, "NULL": -1, "SHAPE": -2, "TILE": -3, "PARAM": -4, "DEVICE": -5, 
 EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qflash_attention",
            "qflash_attention_static",
            "qflash_attention_per_head", "qflash_dynamic_workspace_bytes", "qflash_attention_dynamic",
+           "qflash_dynamic_bias_workspace_bytes", "qflash_attention_dynamic_bias",
            "qflash_packed_bias_bytes", "qflash_pack_bias", "qflash_attention_packed_bias",
            "qflash_plan_query", "qflash_plan_unit", "qflash_cache_query",
            "qflash_destroy", "qflash_strerror"]
@@ -93,6 +94,11 @@ def load_library():
         lib.qflash_attention_per_head.restype = ci
         lib.qflash_dynamic_workspace_bytes.restype = ctypes.c_size_t
         lib.qflash_dynamic_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        lib.qflash_dynamic_bias_workspace_bytes.restype = ctypes.c_size_t
+        lib.qflash_dynamic_bias_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        lib.qflash_attention_dynamic_bias.restype = ci
+        lib.qflash_attention_dynamic_bias.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp,
+                                                      ctypes.c_size_t, vp]
         lib.qflash_attention_dynamic.restype = ci
         lib.qflash_attention_dynamic.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp,
                                                  ctypes.c_size_t, vp]
@@ -299,12 +305,29 @@ def qflash_dynamic_workspace_bytes(B: int, H: int, N: int, d: int) -> int:
     return int(load_library().qflash_dynamic_workspace_bytes(int(B), int(H), int(N), int(d)))
 
 
+def qflash_dynamic_bias_workspace_bytes(B: int, H: int, N: int, d: int, bias_B: int, bias_H: int) -> int:
+    return int(load_library().qflash_dynamic_bias_workspace_bytes(int(B), int(H), int(N), int(d), int(bias_B), int(bias_H)))
+
+
 def qflash_attention_dynamic(ctx: int, Qf, Kf, Vf, O, kv_tile: int, workspace, info=None,
-                             out_round: int = 0, stream: Optional[int] = None) -> None:
+                             out_round: int = 0, stream: Optional[int] = None, bias_real=None, excluded=None) -> None:
     """Quantise float32 CUDA tensors Qf, Kf, Vf [B,H,N,d] on the GPU and run the forward pass.
-    ``workspace``: uint8 CUDA tensor of at least ``qflash_dynamic_workspace_bytes`` bytes;
-    ``info``: None or a uint8 CUDA tensor of ``ctypes.sizeof(DynamicInfo)`` bytes."""
+    ``workspace``: uint8 CUDA tensor of at least ``qflash_dynamic_workspace_bytes`` bytes
+    (``qflash_dynamic_bias_workspace_bytes`` with a bias);
+    ``info``: None or a uint8 CUDA tensor of ``ctypes.sizeof(DynamicInfo)`` bytes;
+    ``bias_real`` / ``excluded``: None, or float32 / uint8 CUDA tensors [bias_B,bias_H,N,N] (a bias in
+    real units and an exclusion mask: qflash_attention_dynamic_bias)."""
     import torch
+    ref = bias_real if bias_real is not None else excluded
+    if ref is not None:
+        if bias_real is not None and (bias_real.dtype != torch.float32 or not bias_real.is_cuda
+                                      or not bias_real.is_contiguous() or bias_real.dim() != 4):
+            raise ValueError("bias_real must be a contiguous float32 CUDA tensor [bias_B,bias_H,N,N]")
+        if excluded is not None and (excluded.dtype != torch.uint8 or not excluded.is_cuda
+                                     or not excluded.is_contiguous() or excluded.shape != ref.shape):
+            raise ValueError("excluded must be a contiguous uint8 CUDA tensor of the bias shape")
+        if tuple(ref.shape[2:]) != (Qf.shape[2], Qf.shape[2]):
+            raise ValueError("bias must be [bias_B,bias_H,N,N]")
     for name, t in (("Qf", Qf), ("Kf", Kf), ("Vf", Vf)):
         if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4 \
                 or t.shape != Qf.shape:
@@ -319,6 +342,14 @@ def qflash_attention_dynamic(ctx: int, Qf, Kf, Vf, O, kv_tile: int, workspace, i
     B, H, N, d = Qf.shape
     if stream is None:
         stream = torch.cuda.current_stream(Qf.device).cuda_stream
+    if ref is not None:
+        rc = load_library().qflash_attention_dynamic_bias(
+            ctypes.c_void_p(ctx), _ptr(Qf), _ptr(Kf), _ptr(Vf), _ptr(O), _ptr(bias_real), _ptr(excluded),
+            int(ref.shape[0]), int(ref.shape[1]), int(B), int(H), int(N), int(d), int(kv_tile), int(out_round),
+            _ptr(info), _ptr(workspace), int(workspace.numel()), ctypes.c_void_p(stream))
+        if rc != 0:
+            raise QFlashError(rc, "qflash_attention_dynamic_bias")
+        return
     rc = load_library().qflash_attention_dynamic(
         ctypes.c_void_p(ctx), _ptr(Qf), _ptr(Kf), _ptr(Vf), _ptr(O), int(B), int(H), int(N), int(d),
         int(kv_tile), int(out_round), _ptr(info), _ptr(workspace), int(workspace.numel()),
@@ -388,8 +419,10 @@ class Context:
     def attention_packed_bias(self, Q, K, V, O, params, kv_tile, packed, bias_B, bias_H, stream=None):
         qflash_attention_packed_bias(self.handle, Q, K, V, O, params, kv_tile, packed, bias_B, bias_H, stream)
 
-    def attention_dynamic(self, Qf, Kf, Vf, O, kv_tile, workspace, info=None, out_round=0, stream=None):
-        qflash_attention_dynamic(self.handle, Qf, Kf, Vf, O, kv_tile, workspace, info, out_round, stream)
+    def attention_dynamic(self, Qf, Kf, Vf, O, kv_tile, workspace, info=None, out_round=0, stream=None,
+                          bias_real=None, excluded=None):
+        qflash_attention_dynamic(self.handle, Qf, Kf, Vf, O, kv_tile, workspace, info, out_round, stream,
+                                 bias_real, excluded)
 
     def close(self):
         if self.handle is not None:

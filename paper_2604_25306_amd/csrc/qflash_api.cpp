@@ -273,7 +273,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         // the stream, which also decides whether there is one (mode 3 reads that decision per
         // workgroup; without mode 3 the table is simply not looked at).
         const bool use_table = table_wanted;
-        if (use_table && dyn_table && a.resident && !bias && table_fits(a, d, kTableMaxBytes, lds_limit)) {
+        if (use_table && dyn_table && a.resident && table_fits(a, d, kTableMaxBytes, lds_limit)) {
             a.exp_mode = 3;
             a.lut_bytes_max = kTableMaxBytes;
         }
@@ -554,10 +554,11 @@ extern "C" size_t qflash_dynamic_workspace_bytes(int B, int H, int N, int d) {
     return 3 * align256(n) + align256(sizeof(QflashHeadConsts)) + dyn_scratch_bytes(n) + align256(kTableMaxBytes);
 }
 
-extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const float* Kf, const float* Vf,
-                                        int8_t* O, int B, int H, int N, int d, int kv_tile, int out_round,
-                                        qflash_dynamic_info* info, void* workspace, size_t workspace_bytes,
-                                        void* hip_stream) {
+namespace {
+
+int dynamic_impl(qflash_ctx* ctx, const float* Qf, const float* Kf, const float* Vf, int8_t* O, const float* bias_real,
+                 const uint8_t* excluded, int bias_B, int bias_H, int B, int H, int N, int d, int kv_tile, int out_round,
+                 qflash_dynamic_info* info, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!ctx) return QFLASH_ERR_NULL;
     int device, lds_limit, n_cu;
     {
@@ -567,21 +568,34 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
         lds_limit = ctx->lds_limit;
         n_cu = ctx->n_cu;
     }
+    const bool with_bias = bias_real || excluded;
     if (!Qf || !Kf || !Vf || !O || !workspace) return QFLASH_ERR_NULL;
     if (d != 32 && d != 64) return QFLASH_ERR_SHAPE;
     if (B < 1 || H < 1 || N < 1 || N > QFLASH_MAX_N) return QFLASH_ERR_SHAPE;
     if ((int64_t)B * H * N * d >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
-    if (workspace_bytes < qflash_dynamic_workspace_bytes(B, H, N, d)) return QFLASH_ERR_SHAPE;
+    size_t need = qflash_dynamic_workspace_bytes(B, H, N, d);
+    if (with_bias) {
+        if (bias_B < 1 || bias_H < 1) return QFLASH_ERR_SHAPE;
+        if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return QFLASH_ERR_SHAPE;
+        if (qflash_packed_bias_words(bias_B * bias_H, N) >= ((int64_t)1 << 29)) return QFLASH_ERR_SHAPE;
+        need = qflash_dynamic_bias_workspace_bytes(B, H, N, d, bias_B, bias_H);
+    }
+    if (need == 0 || workspace_bytes < need) return QFLASH_ERR_SHAPE;
     if (kv_tile != 64 && kv_tile != 128) return QFLASH_ERR_TILE;
     if (out_round != 0 && out_round != 1) return QFLASH_ERR_PARAM;
     if (((uintptr_t)Qf | (uintptr_t)Kf | (uintptr_t)Vf | (uintptr_t)O | (uintptr_t)workspace) & 15u) return QFLASH_ERR_ALIGN;
+    if (bias_real && ((uintptr_t)bias_real & 3u)) return QFLASH_ERR_ALIGN;
     if (info && ((uintptr_t)info & 7u)) return QFLASH_ERR_ALIGN;
     {
         // everything the attention launch would refuse is refused here, before the quantising kernels
         // are enqueued
+        static const int32_t some_bias = 0;
         QflashKernelArgs probe;
         std::memset(&probe, 0, sizeof probe);
-        probe.B = B; probe.H = H; probe.N = N; probe.bias_B = 1; probe.bias_H = 1; probe.n_cu = n_cu;
+        probe.B = B; probe.H = H; probe.N = N; probe.n_cu = n_cu;
+        probe.bias = with_bias ? &some_bias : nullptr;
+        probe.bias_B = with_bias ? bias_B : 1;
+        probe.bias_H = with_bias ? bias_H : 1;
         if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &probe) != 0) return QFLASH_ERR_SHAPE;
     }
 
@@ -593,6 +607,7 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
     QflashHeadConsts* hc_dev = (QflashHeadConsts*)(Vo + align256(n));
     float* scratch = (float*)((int8_t*)hc_dev + align256(sizeof(QflashHeadConsts)));
     uint8_t* dyn_table = (uint8_t*)scratch + dyn_scratch_bytes(n);    // kTableMaxBytes: a weight table made on the GPU
+    int32_t* packed = (int32_t*)(ws + qflash_dynamic_workspace_bytes(B, H, N, d));   // with_bias only
 
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess) { (void)hipGetLastError(); return QFLASH_ERR_DEVICE; }
@@ -602,10 +617,42 @@ extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const 
     }
     int rc = qflash_launch_dynamic_front(Qf, Kf, Vf, Qo, Ko, Vo, (long long)n, std::sqrt((double)d), out_round,
                                          scratch, hc_dev, info, dyn_table, kTableMaxBytes, hip_stream);
+    if (rc == 0 && with_bias)
+        rc = qflash_launch_dynamic_bias(bias_real, excluded, bias_B * bias_H, N, packed, scratch, (long long)n,
+                                        std::sqrt((double)d), hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
-    return attention_impl(ctx, Qo, Ko, Vo, O, nullptr, 0, 0, B, H, N, d, kv_tile, nullptr, false, hip_stream,
-                          hc_dev, out_round, false, dyn_table);
+    return attention_impl(ctx, Qo, Ko, Vo, O, with_bias ? packed : nullptr, with_bias ? bias_B : 0, with_bias ? bias_H : 0,
+                          B, H, N, d, kv_tile, nullptr, false, hip_stream, hc_dev, out_round, with_bias, dyn_table);
+}
+
+}  // namespace
+
+extern "C" int qflash_attention_dynamic(qflash_ctx* ctx, const float* Qf, const float* Kf, const float* Vf,
+                                        int8_t* O, int B, int H, int N, int d, int kv_tile, int out_round,
+                                        qflash_dynamic_info* info, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream) {
+    return dynamic_impl(ctx, Qf, Kf, Vf, O, nullptr, nullptr, 0, 0, B, H, N, d, kv_tile, out_round, info, workspace,
+                        workspace_bytes, hip_stream);
+}
+
+extern "C" size_t qflash_dynamic_bias_workspace_bytes(int B, int H, int N, int d, int bias_B, int bias_H) {
+    const size_t base = qflash_dynamic_workspace_bytes(B, H, N, d);
+    if (base == 0 || bias_B < 1 || bias_H < 1) return 0;
+    if ((int64_t)bias_B * bias_H * N * N >= ((int64_t)1 << 31)) return 0;
+    const long long words = qflash_packed_bias_words(bias_B * bias_H, N);
+    if (words >= (1ll << 29)) return 0;
+    return base + 16 * (size_t)words;
+}
+
+extern "C" int qflash_attention_dynamic_bias(qflash_ctx* ctx, const float* Qf, const float* Kf, const float* Vf,
+                                             int8_t* O, const float* bias_real, const uint8_t* excluded, int bias_B,
+                                             int bias_H, int B, int H, int N, int d, int kv_tile, int out_round,
+                                             qflash_dynamic_info* info, void* workspace, size_t workspace_bytes,
+                                             void* hip_stream) {
+    if (!bias_real && !excluded) return QFLASH_ERR_NULL;
+    return dynamic_impl(ctx, Qf, Kf, Vf, O, bias_real, excluded, bias_B, bias_H, B, H, N, d, kv_tile, out_round, info,
+                        workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" const char* qflash_strerror(int code) {

@@ -10,6 +10,8 @@
 //                 x_hat = clip(rint(x * r), -127, 127), r = float32(127) / max|x|: one float32
 //                 division per tensor, one float32 multiplication and one round-half-to-even per
 //                 element (the precision the rounding decision is defined in)
+//   2b. bias      (optional) a bias in real units and an exclusion mask are brought to the integer
+//                 score unit of the scales just found and written in the packed layout
 //   3. attention  the usual kernel, reading its constants from the device structure of step 2
 //
 // Steps 1 and 2 stream the float32 tensors once each and are bound by HBM: 12 B read in step 1
@@ -139,7 +141,53 @@ __global__ __launch_bounds__(256) void qflash_dyn_quantize(const float* q, const
     }
 }
 
+// Real bias and exclusion mask -> int32 bias in the lane-major packed layout the attention kernel
+// reads (see qflash_pack_bias_kernel for the layout), in the score unit of the scales just found:
+//   unit = (s_Q s_K) / sqrt(d),  b_hat = clip(floor(double(b) / unit + 0.5), -(2^20 - 1), 2^20 - 1)
+// evaluated in float64 with one rounding per operation (the precision the decision is defined in).
+// One thread per 16-byte word; every workgroup first finishes the abs-max reduction of Q and K.
+__global__ __launch_bounds__(256) void qflash_dyn_bias(const float* __restrict__ bias, const uint8_t* __restrict__ mask,
+                                                      int32_t* __restrict__ packed, int N, long long n_words,
+                                                      const float* partial, int n_partial, double sqrt_d) {
+    __shared__ float wmax[4];
+    const float aq = wg_max(partial, n_partial, wmax);
+    const float ak = wg_max(partial + n_partial, n_partial, wmax);
+    const double sq = aq == 0.0f ? 1.0 : __ddiv_rn((double)aq, 127.0);
+    const double sk = ak == 0.0f ? 1.0 : __ddiv_rn((double)ak, 127.0);
+    const double unit = __ddiv_rn(__dmul_rn(sq, sk), sqrt_d);
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_words) return;
+    const int nb = (N + 31) / 32;
+    const int lane = (int)(t & 63), a4 = (int)((t >> 6) & 3);
+    const long long blk = t >> 8;
+    const int cb = (int)(blk % nb), rb = (int)((blk / nb) % nb);
+    const long long slice = blk / ((long long)nb * nb);
+    const int li = lane & 31, g = lane >> 5;
+    const int row = min(32 * rb + li, N - 1), col0 = 32 * cb + 8 * a4 + 4 * g;
+    const long long base = (slice * N + row) * (long long)N;
+    int32_t w[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        int32_t v = INT32_MIN;
+        if (col0 + b < N && !(mask && mask[base + col0 + b] != 0)) {
+            const double x = bias ? (double)bias[base + col0 + b] : 0.0;
+            const double r = floor(__dadd_rn(__ddiv_rn(x, unit), 0.5));
+            v = (int32_t)fmin(fmax(r, -1048575.0), 1048575.0);
+        }
+        w[b] = v;
+    }
+    *(int4*)(packed + 4 * t) = int4{w[0], w[1], w[2], w[3]};
+}
+
 }  // namespace
+
+int qflash_launch_dynamic_bias(const float* bias, const uint8_t* mask, int slices, int N, int32_t* packed,
+                               const float* scratch, long long n, double sqrt_d, void* stream) {
+    const long long n_words = qflash_packed_bias_words(slices, N);
+    hipLaunchKernelGGL(qflash_dyn_bias, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, bias, mask,
+                       packed, N, n_words, scratch, qflash_dynamic_partials(n), sqrt_d);
+    return (int)hipGetLastError();
+}
 
 int qflash_dynamic_partials(long long n) {
     // enough workgroups to keep every HBM channel busy (two per compute unit and tensor); each

@@ -141,3 +141,8 @@ int qflash_launch_dynamic_front(const float* Qf, const float* Kf, const float* V
                                 long long n, double sqrt_d, int out_round, float* scratch,
                                 QflashHeadConsts* hc_dev, qflash_dynamic_info* info, uint8_t* table, int table_max,
                                 void* stream);
+// Enqueue (after qflash_launch_dynamic_front on the same stream, same scratch and n) the kernel that
+// converts a real bias (float32 [slices,N,N] or null) and exclusion mask (uint8, same shape, or
+// null) into the packed int32 bias of the scales found by the abs-max step.
+int qflash_launch_dynamic_bias(const float* bias, const uint8_t* mask, int slices, int N, int32_t* packed,
+                               const float* scratch, long long n, double sqrt_d, void* stream);

@@ -449,14 +449,19 @@ def test_per_head_errors(gpu):
 # ------------------------------------------------- dynamic quantisation in front of the kernel
 
 
-def run_dynamic(gpu, Qf, Kf, Vf, tile, out_round=0):
+def run_dynamic(gpu, Qf, Kf, Vf, tile, out_round=0, bias_real=None, excluded=None):
     torch, qf, ctx = gpu
     dev = torch.device("cuda:0")
     tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev) for x in (Qf, Kf, Vf))
     tO = torch.full(Qf.shape, 0x55, dtype=torch.int8, device=dev)
-    ws = torch.empty(qf.qflash_dynamic_workspace_bytes(*Qf.shape), dtype=torch.uint8, device=dev)
+    ref = bias_real if bias_real is not None else excluded
+    nbytes = qf.qflash_dynamic_workspace_bytes(*Qf.shape) if ref is None else \
+        qf.qflash_dynamic_bias_workspace_bytes(*Qf.shape, ref.shape[0], ref.shape[1])
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     info = torch.zeros(ctypes.sizeof(qf.DynamicInfo), dtype=torch.uint8, device=dev)
-    ctx.attention_dynamic(tq, tk, tv, tO, tile, ws, info=info, out_round=out_round)
+    tb = torch.from_numpy(np.ascontiguousarray(bias_real, dtype=np.float32)).to(dev) if bias_real is not None else None
+    tm = torch.from_numpy(np.ascontiguousarray(excluded, dtype=np.uint8)).to(dev) if excluded is not None else None
+    ctx.attention_dynamic(tq, tk, tv, tO, tile, ws, info=info, out_round=out_round, bias_real=tb, excluded=tm)
     torch.cuda.synchronize()
     inf = qf.DynamicInfo.from_buffer_copy(info.cpu().numpy().tobytes())
     n = Qf.size
@@ -517,6 +522,59 @@ def test_dynamic_degenerate_and_out_of_window(gpu):
     with pytest.raises(qf.QFlashError) as e:
         ctx.attention_dynamic(t, t, t, o, 96, ws)
     assert e.value.code == qf.ERR["TILE"]
+
+
+@pytest.mark.parametrize("shape,bias_bh,tile", [((6, 3, 49, 32), (2, 3), 64), ((2, 2, 197, 64), (1, 1), 64),
+                                                 ((2, 2, 300, 64), (2, 1), 128), ((1, 1, 1, 32), (1, 1), 64)])
+def test_dynamic_with_real_bias_and_mask(gpu, shape, bias_bh, tile):
+    """A bias in real units and an exclusion mask, converted on the GPU to the score unit of the
+    scales found on the fly: equal to the oracle's conversion and attention, bit for bit; mask only
+    and bias only as well."""
+    rng = np.random.default_rng(4100 + shape[2])
+    Qf, Kf, Vf = (rng.standard_normal(shape).astype(np.float32) for _ in range(3))
+    N = shape[2]
+    b = (rng.standard_normal(bias_bh + (N, N)) * 0.6).astype(np.float32)
+    m = (rng.random(bias_bh + (N, N)) < 0.25).astype(np.uint8)
+    m[..., 0] = 0                                   # keep one key per row
+    if N > 5:
+        m[0, 0, 5, :] = 1                           # ... except for one fully excluded row
+    for bias_real, excluded in ((b, m), (b, None), (None, m)):
+        ref, rinfo = oracle.qflash_attention_dynamic(Qf, Kf, Vf, tile, bias_real=bias_real, excluded=excluded)
+        out, inf, _ = run_dynamic(gpu, Qf, Kf, Vf, tile, bias_real=bias_real, excluded=excluded)
+        assert inf.status == 0 and inf.params.astuple() == rinfo["params"].astuple()
+        assert_same(out, ref, "dynamic bias %s %s" % (bias_real is not None, excluded is not None))
+
+
+def test_dynamic_bias_windowed_workload_and_errors(gpu):
+    torch, qf, ctx = gpu
+    from workloads import make_float_qkv, make_float_window_bias
+    Qf, Kf, Vf = make_float_qkv("swin_t_s1_b64", batch=256)
+    bias_real, excluded = make_float_window_bias("swin_t_s1_b64")
+    ref, _ = oracle.qflash_attention_dynamic(Qf, Kf, Vf, 64, bias_real=bias_real, excluded=excluded)
+    out, inf, _ = run_dynamic(gpu, Qf, Kf, Vf, 64, bias_real=bias_real, excluded=excluded)
+    assert inf.status == 0
+    assert_same(out, ref, "swin stage 1 from float inputs")
+    # argument errors of the new entry point
+    dev = torch.device("cuda:0")
+    shape = (1, 2, 40, 32)
+    t = torch.zeros(shape, dtype=torch.float32, device=dev)
+    o = torch.zeros(shape, dtype=torch.int8, device=dev)
+    bias = torch.zeros((1, 1, 40, 40), dtype=torch.float32, device=dev)
+    ws_small = torch.empty(qf.qflash_dynamic_workspace_bytes(*shape), dtype=torch.uint8, device=dev)
+    with pytest.raises(qf.QFlashError) as e:           # workspace without room for the converted bias
+        ctx.attention_dynamic(t, t, t, o, 64, ws_small, bias_real=bias)
+    assert e.value.code == qf.ERR["SHAPE"]
+    assert qf.qflash_dynamic_bias_workspace_bytes(*shape, 0, 1) == 0
+    lib = qf.load_library()
+    ws = torch.empty(qf.qflash_dynamic_bias_workspace_bytes(*shape, 1, 1), dtype=torch.uint8, device=dev)
+    vp = ctypes.c_void_p
+    args = [vp(ctx.handle), vp(t.data_ptr()), vp(t.data_ptr()), vp(t.data_ptr()), vp(o.data_ptr())]
+    tail = [1, 2, 40, 32, 64, 0, None, vp(ws.data_ptr()), ws.numel(), None]
+    assert lib.qflash_attention_dynamic_bias(*args, None, None, 1, 1, *tail) == qf.ERR["NULL"]
+    assert lib.qflash_attention_dynamic_bias(*args, vp(bias.data_ptr()), None, 0, 1, *tail) == qf.ERR["SHAPE"]
+    assert lib.qflash_attention_dynamic_bias(*args, vp(bias.data_ptr() + 2), None, 1, 1, *tail) == qf.ERR["ALIGN"]
+    assert lib.qflash_attention_dynamic_bias(*args, vp(bias.data_ptr()), None, 1, 1, *tail) == 0
+    torch.cuda.synchronize()
 
 
 def test_dynamic_headline_shape_full_size(gpu):
