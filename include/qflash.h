@@ -320,6 +320,13 @@ int qflash_attention_dynamic_bias(qflash_ctx* ctx,
  *                    wavefronts_per_pair is the number of wavefronts of a workgroup, query_blocks the
  *                    32-row blocks of a pair, units = workgroups, and workgroup w takes pairs
  *                    [w * pairs_per_workgroup, (w + 1) * pairs_per_workgroup).
+ *                    4: windowed attention (33 <= N <= 64, d = 32, one KV tile, no bias or a bias
+ *                    in the packed layout whose extents divide B and H, one set of constants,
+ *                    Algorithm 1 only): persistent workgroups, one per compute unit, whose wavefronts
+ *                    each work through a run of pairs that share a bias slice (the query assumes
+ *                    that a bias would be packed).  For kernel 4: pairs_per_workgroup = pairs a
+ *                    workgroup works through, wavefronts_per_pair = 2 (one per half of the rows),
+ *                    units = workgroups.
  *   pairs_per_workgroup, wavefronts_per_pair, query_blocks (workgroups a pair is split over),
  *   units (pieces of work = workgroups that have rows), workgroups (launched; a few may be idle),
  *   tile_by_tile (1: KV tiles staged one ahead of their use), bias_period_units (0, or the number of

@@ -164,6 +164,7 @@ namespace {
 
 // Whether the planned launch can hold a weight table of table_bytes in LDS and copying it pays.
 bool table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds_limit) {
+    if (a.win_mode) return table_bytes <= a.win_table_lds;      // staged once per compute unit
     if (a.cu_mode) return table_bytes <= a.cu_table_lds && 4ll * a.cu_heads * a.N * d >= (long long)table_bytes;
     return qflash_table_fits(a, d, table_bytes, lds_limit) != 0;
 }
@@ -249,7 +250,10 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
             if (x_p + 16 <= kTableMaxBytes) table_hint = ((int)x_p + 1 + 15) & ~15;
         }
         // a table only pays while it is smaller than the Q, K, V, O bytes of the workgroup
-        if (qmax) a.cu_mode = 0;          // the whole-compute-unit kernel exists for Algorithm 1 only
+        a.win_mode = 0;
+        if (!qmax && qflash_plan_win(d, kv_tile, lds_limit, table_hint, &a) == 0 && table_hint > 0)
+            qflash_plan_win(d, kv_tile, lds_limit, 0, &a);
+        if (qmax || a.win_mode) a.cu_mode = 0;          // (the whole-compute-unit kernel exists for Algorithm 1 only)
         else if (!qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, table_hint, &a) && table_hint > 0)
             qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, 0, &a);
     }
@@ -384,15 +388,19 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         } else {
             for (int h = 0; h < n_p; ++h) { a.hc[h].lut = nullptr; a.hc[h].lut_bytes = 0; a.hc[h].lut_xp = 0; }
         }
-        if (rc == 0) rc = a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream) : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+        if (rc == 0) rc = a.win_mode  ? qflash_launch_fwd_win(a, lds_limit, hip_stream)
+                          : a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream)
+                                      : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
         ctx->last_mode = a.exp_mode == 2 ? QFLASH_WEIGHTS_TABLE : a.exp_mode == 3 ? QFLASH_WEIGHTS_MIXED : QFLASH_WEIGHTS_ARITHMETIC;
-        ctx->last_kernel = a.cu_mode ? 3 : !a.resident ? 0 : a.ring ? 2 : 1;
+        ctx->last_kernel = a.win_mode ? 4 : a.cu_mode ? 3 : !a.resident ? 0 : a.ring ? 2 : 1;
         lk.unlock();
         if (cur != device) (void)hipSetDevice(cur);
         if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
         return QFLASH_OK;
     }
-    if (rc == 0) rc = a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream) : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+    if (rc == 0) rc = a.win_mode  ? qflash_launch_fwd_win(a, lds_limit, hip_stream)
+                          : a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream)
+                                      : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
     return QFLASH_OK;
@@ -451,6 +459,16 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
     a.n_cu = n_cu;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
     std::memset(out, 0, sizeof *out);
+    a.bias_packed = has_bias ? 1 : 0;      // (a bias is taken to be in the packed layout, the only one kernel 4 reads)
+    if (!qmax && qflash_plan_win(d, kv_tile, lds_limit, kPlanQueryTableBytes, &a)) {
+        out->kernel = 4;
+        out->pairs_per_workgroup = a.win_streams * a.win_chunk;
+        out->wavefronts_per_pair = 2;
+        out->query_blocks = 2;
+        out->units = a.win_groups;
+        out->workgroups = a.win_groups;
+        return QFLASH_OK;
+    }
     if (!qmax && qflash_plan_cu(B * H, N, d, kv_tile, lds_limit, kPlanQueryTableBytes, &a)) {
         out->kernel = 3;
         out->pairs_per_workgroup = a.cu_heads;
@@ -491,7 +509,7 @@ extern "C" int qflash_cache_query(qflash_ctx* ctx, qflash_cache_info* out) {
 
 extern "C" int qflash_plan_unit(const qflash_plan_info* plan, int workgroup) {
     if (!plan || workgroup < 0 || workgroup >= plan->workgroups) return -1;
-    if (plan->kernel == 3) return workgroup;
+    if (plan->kernel == 3 || plan->kernel == 4) return workgroup;
     const int unit = qflash_unit_of_workgroup(workgroup, plan->units_per_xcd, plan->bias_period_units);
     return unit < plan->units ? unit : -1;
 }

@@ -52,6 +52,12 @@ struct QflashKernelArgs {
     int cu_groups;           // workgroups
     int cu_waves;            // wavefronts per workgroup (at most 16)
     int cu_table_lds;        // LDS bytes reserved for the weight table (a multiple of 1 KiB)
+    // windowed-attention kernel (qflash_plan_win): 1 if the launch takes it
+    int win_mode;
+    int win_streams;         // pairs of wavefronts (one per half of the query rows) per workgroup, at most 8
+    int win_chunk;           // consecutive pairs (in slice-major order) each pair of wavefronts works through
+    int win_groups;          // workgroups
+    int win_table_lds;       // LDS bytes reserved for the weight table (a multiple of 1 KiB)
 #ifdef QF_TRACE
     unsigned long long* trace;   // instrumented builds only: [workgroup][wavefront][16] timestamps
 #endif
@@ -115,6 +121,14 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
 // table_bytes (0: none), and fills the cu_* fields.  Reads bias, per_head, n_cu (0: 256).  Returns cu_mode.
 int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_bytes, QflashKernelArgs* args);
 int qflash_launch_fwd_cu(const QflashKernelArgs& args, int lds_limit, void* stream);
+
+// The persistent kernel for windowed attention (33 to 64 tokens, 32 features, one KV tile, no bias or a
+// packed bias whose extents divide B and H, one set of constants, Algorithm 1 only): decides whether
+// the launch takes it and fills the win_* fields.  Reads bias, bias_packed, bias_B, bias_H, B, H, N,
+// per_head, qmax, n_cu (0: 256).  Returns win_mode.
+int qflash_plan_win(int d, int kv_tile, int lds_limit, int table_bytes, QflashKernelArgs* args);
+int qflash_launch_fwd_win(const QflashKernelArgs& args, int lds_limit, void* stream);
+size_t qflash_win_lds_bytes(int streams, int table_bytes);
 
 // GPUs per process for which per-device launch set-up is remembered.
 constexpr int kQflashMaxDevices = 64;

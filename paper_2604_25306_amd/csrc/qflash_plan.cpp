@@ -188,3 +188,33 @@ int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_b
     a->cu_table_lds = (table_bytes + 1023) & ~1023;
     return 1;
 }
+
+// LDS bytes of the windowed-attention kernel: the table (rounded up to 1 KiB) and two 2 KiB V
+// buffers per wavefront.
+size_t qflash_win_lds_bytes(int streams, int table_bytes) {
+    return (((size_t)table_bytes + 1023) & ~(size_t)1023) + (size_t)streams * 2 * 4096;
+}
+
+int qflash_plan_win(int d, int kv_tile, int lds_limit, int table_bytes, QflashKernelArgs* a) {
+    (void)kv_tile;                      // a single KV tile either way: 64 and 128 give the same result
+    a->win_mode = 0;
+    if (d != 32 || a->N <= 32 || a->N > 64 || a->per_head || a->qmax) return 0;
+    if (a->bias && (!a->bias_packed || a->bias_B < 1 || a->bias_H < 1 || a->B % a->bias_B != 0 || a->H % a->bias_H != 0)) return 0;
+    const long long T = (long long)a->B * a->H;
+    const int cus = a->n_cu > 0 ? a->n_cu : 256;
+    // as many runs as there are pairs, up to eight per compute unit; equal shares
+    long long runs = T < 8ll * cus ? T : 8ll * cus;
+    const long long chunk = (T + runs - 1) / runs;
+    runs = (T + chunk - 1) / chunk;
+    int streams = (int)((runs + cus - 1) / cus);
+    if (streams > 8) streams = 8;
+    const long long groups = (runs + streams - 1) / streams;
+    if (chunk >= (1ll << 30) || groups >= (1ll << 30)) return 0;
+    if (qflash_win_lds_bytes(streams, table_bytes) > (size_t)lds_limit) return 0;
+    a->win_mode = 1;
+    a->win_streams = streams;
+    a->win_chunk = (int)chunk;
+    a->win_groups = (int)groups;
+    a->win_table_lds = (table_bytes + 1023) & ~1023;
+    return 1;
+}

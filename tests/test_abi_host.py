@@ -146,6 +146,11 @@ def test_plan_covers_every_unit_exactly_once(lib):
             assert c[3] == 64 and c[4] == 64 and c[2] <= 256 and c[5] == 0, c
             assert 1 <= plan.wavefronts_per_pair <= 16 and plan.query_blocks * 32 >= c[2], c
             continue
+        if plan.kernel == 4:        # windowed attention: persistent workgroups, runs of pairs per wavefront pair
+            assert plan.units == plan.workgroups <= 256 and plan.workgroups * plan.pairs_per_workgroup >= pairs, c
+            assert c[3] == 32 and 32 < c[2] <= 64 and plan.wavefronts_per_pair == 2, c
+            assert c[5] == 0 or (c[0] % c[5] == 0 and c[1] % c[6] == 0), c
+            continue
         assert plan.workgroups % 8 == 0 and plan.workgroups >= plan.units, c
         assert plan.bias_period_units % 8 == 0, c
         pairs = c[0] * c[1]
@@ -167,11 +172,14 @@ def test_plan_of_the_benchmark_shapes(lib):
     assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 4, 5)
     p = qf.qflash_plan_query(None, 16, 16, 577, 64, 64)        # same turns either way: the larger workgroup
     assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 7, 3)
-    p = qf.qflash_plan_query(None, 4096, 3, 49, 32, 64, 64, 3)  # four windows per workgroup, bias period 64*3/4
-    assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.bias_period_units) == (1, 4, 2, 48)
+    p = qf.qflash_plan_query(None, 4096, 3, 49, 32, 64, 64, 3)  # windowed: 256 persistent workgroups, 8 runs of 6 pairs each
+    assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.workgroups) == (4, 48, 2, 256)
+    p = qf.qflash_plan_query(None, 4097, 3, 49, 32, 64, 64, 3)  # the bias extents do not divide the batch: the resident kernel,
+    assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.bias_period_units) == (1, 4, 2, 48)   # four windows per workgroup
     # XCD x = workgroup % 8 only ever meets an eighth of the bias slices
     for x in range(8):
-        slices = {(qf.qflash_plan_unit(p, wg) * 4 + s) % 192 for wg in range(x, p.workgroups, 8) for s in range(4)}
+        slices = {(qf.qflash_plan_unit(p, wg) * 4 + s) % 192 for wg in range(x, p.workgroups, 8) for s in range(4)
+                  if qf.qflash_plan_unit(p, wg) >= 0}
         assert len(slices) == 24, x
     p = qf.qflash_plan_query(None, 1, 1, 4096, 32, 64)           # too long for LDS at d = 32: streamed
     assert p.kernel == 0
