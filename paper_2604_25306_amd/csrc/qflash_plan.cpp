@@ -189,10 +189,10 @@ int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_b
     return 1;
 }
 
-// LDS bytes of the windowed-attention kernel: the table (rounded up to 1 KiB) and two 2 KiB V
-// buffers per wavefront.
+// LDS bytes of the windowed-attention kernel: the table (rounded up to 1 KiB) and, per wavefront
+// (two to a stream), two sets of V, K and 32 query rows (5 KiB each).
 size_t qflash_win_lds_bytes(int streams, int table_bytes) {
-    return (((size_t)table_bytes + 1023) & ~(size_t)1023) + (size_t)streams * 2 * 4096;
+    return (((size_t)table_bytes + 1023) & ~(size_t)1023) + (size_t)streams * 2 * 2 * 5120;
 }
 
 int qflash_plan_win(int d, int kv_tile, int lds_limit, int table_bytes, QflashKernelArgs* a) {
@@ -202,12 +202,16 @@ int qflash_plan_win(int d, int kv_tile, int lds_limit, int table_bytes, QflashKe
     if (a->bias && (!a->bias_packed || a->bias_B < 1 || a->bias_H < 1 || a->B % a->bias_B != 0 || a->H % a->bias_H != 0)) return 0;
     const long long T = (long long)a->B * a->H;
     const int cus = a->n_cu > 0 ? a->n_cu : 256;
-    // as many runs as there are pairs, up to eight per compute unit; equal shares
-    long long runs = T < 8ll * cus ? T : 8ll * cus;
+    // as many runs as there are pairs, up to eight per compute unit (fewer where the table leaves
+    // less LDS); equal shares
+    int max_streams = 8;
+    while (max_streams > 0 && qflash_win_lds_bytes(max_streams, table_bytes) > (size_t)lds_limit) --max_streams;
+    if (max_streams == 0) return 0;
+    long long runs = T < (long long)max_streams * cus ? T : (long long)max_streams * cus;
     const long long chunk = (T + runs - 1) / runs;
     runs = (T + chunk - 1) / chunk;
     int streams = (int)((runs + cus - 1) / cus);
-    if (streams > 8) streams = 8;
+    if (streams > max_streams) streams = max_streams;
     const long long groups = (runs + streams - 1) / streams;
     if (chunk >= (1ll << 30) || groups >= (1ll << 30)) return 0;
     if (qflash_win_lds_bytes(streams, table_bytes) > (size_t)lds_limit) return 0;

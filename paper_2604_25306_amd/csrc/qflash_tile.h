@@ -447,8 +447,10 @@ __device__ __forceinline__ int clamp_0(int u, int hi) {
     return r;
 }
 
+// normalise_words leaves the lane's contiguous half of the output row (D / 2 bytes: lane g = 0 the
+// first half, g = 1 the second) in out[0 .. D/32); normalise_store also writes it.
 template <int D, int L>
-__device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* Orow, int g, bool round_nearest) {
+__device__ __forceinline__ void normalise_words(const RowState<D>& st, bool round_nearest, v4i* out) {
     constexpr int TB = D / 32;
     static_assert(L == 16 || L == 20, "quotient must be byte aligned");
     const int rs = round_nearest ? 1 : 0;
@@ -491,10 +493,18 @@ __device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* O
         ev[j] = sw[0];
         od[j] = sw[1];
     }
-    int8_t* dst = Orow + g * (D / 2);
 #pragma unroll
     for (int q = 0; q < HALF / 2; ++q)
-        *(v4i*)(dst + 16 * q) = v4i{(int)ev[2 * q], (int)od[2 * q], (int)ev[2 * q + 1], (int)od[2 * q + 1]};
+        out[q] = v4i{(int)ev[2 * q], (int)od[2 * q], (int)ev[2 * q + 1], (int)od[2 * q + 1]};
+}
+
+template <int D, int L>
+__device__ __forceinline__ void normalise_store(const RowState<D>& st, int8_t* Orow, int g, bool round_nearest) {
+    v4i w[D / 32];
+    normalise_words<D, L>(st, round_nearest, w);
+    int8_t* dst = Orow + g * (D / 2);
+#pragma unroll
+    for (int q = 0; q < D / 32; ++q) *(v4i*)(dst + 16 * q) = w[q];
 }
 
 

@@ -10,12 +10,13 @@
 //     pairs.  Pairs are numbered so that a run shares one bias slice (same window position and head
 //     in consecutive images); the 32 bias words of the lane stay in registers, already offset, and
 //     serve as the accumulator input of the first matrix product: adding the bias costs nothing.
-//   - K and Q rows are MFMA operands exactly as they lie in memory (lane (l % 32, l / 32) needs
-//     bytes 16 (l / 32) .. +15 of row l % 32): they go from global memory straight to registers,
-//     one pair ahead of their use.
-//   - V goes to a private 2 KiB LDS buffer (two of them, alternating) by direct global-to-LDS
-//     loads, row-major as in memory, and the V^T operand is read with the transposing 8-bit LDS
-//     read: no transposition in the vector ALU, no LDS write instruction.
+//   - K, V and the wavefront's 32 query rows go to private LDS buffers (5 KiB, two sets,
+//     alternating) by direct global-to-LDS loads, one pair ahead of their use, row-major as in
+//     memory.  K and Q rows are MFMA operands exactly as they lie there (lane (l % 32, l / 32) reads
+//     bytes 16 (l / 32) .. +15 of row l % 32); the V^T operand is read with the transposing 8-bit
+//     LDS read.  No staging registers, no transposition in the vector ALU, no LDS write
+//     instruction, and nothing in flight that the compiler has to count: the only wait of an
+//     iteration is the one at its top.
 // Keys beyond the sequence and excluded pairs carry a large negative accumulator input
 // (-2^29 before the offset), far below every real score, so they fall out of the maximum and get
 // weight 0 without a test.  Scores carry the offset 2^30 (see qflash_tile.h), which turns the
@@ -44,6 +45,7 @@ __device__ __forceinline__ void win_load_1k(const int8_t* g /* uniform */, int l
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_off), "s"((glb_void_w)g) : "memory", "m0");
 }
 
+constexpr int kWinSetBytes = 5 * 1024;     // V, K and 32 query rows of one pair
 constexpr int kWinExcluded = -(1 << 29);   // stands for "takes no part" in the offset representation
 
 struct WinPair {      // where a run stands: pair t of the launch order
@@ -64,8 +66,8 @@ __device__ __forceinline__ void win_body(const QflashKernelArgs& a) {
     const QflashHeadConsts hc = head_consts_or_dev(a, a.hc[0]);
     const ExpConst c = make_exp_const(hc);
 
-    // ---- LDS: [weight table, a.win_table_lds bytes][wavefront w: two V buffers of 2 KiB]; the
-    //      dynamic LDS is the only LDS of the kernel, so the table index is its address
+    // ---- LDS: [weight table, a.win_table_lds bytes][wavefront w: two sets of V (2 KiB), K (2 KiB),
+    //      Q (1 KiB)]; the dynamic LDS is the only LDS of the kernel, so the table index is its address
     const int lds0 = (int)(size_t)(lds_void_w)smem_win;
     const int tbytes = XM == kExpTable ? a.win_table_lds : 0;
     if (XM == kExpTable) {
@@ -109,15 +111,15 @@ __device__ __forceinline__ void win_body(const QflashKernelArgs& a) {
         }
     };
 
-    // ---- per-lane offsets inside a pair (bytes): K rows of the two key blocks, the query row, the
-    //      two 1 KiB pieces of V (clamped to the pair's last 16 bytes: what lands in rows beyond the
-    //      sequence meets weight 0), the V^T operand in LDS, the output row
-    const unsigned koff0 = (unsigned)(min(li, N - 1) * D + 16 * g);
-    const unsigned koff1 = (unsigned)(min(32 + li, N - 1) * D + 16 * g);
+    // ---- per-lane offsets (bytes).  In memory: the two 1 KiB pieces of K and V of a pair and the
+    //      1 KiB of this half's query rows, each clamped to the pair's last 16 bytes (what lands in
+    //      rows beyond the sequence meets weight 0 or is never stored).  In LDS: operand rows, the
+    //      V^T operand.
     const int row = 32 * half + li;
-    const unsigned qoff = (unsigned)(min(row, N - 1) * D + 16 * g);
     const int voff0 = min(16 * lane, N * D - 16), voff1 = min(1024 + 16 * lane, N * D - 16);
-    const int vbuf = lds0 + tbytes + wave * 4096;
+    const int qoff = min(1024 * half + 16 * lane, N * D - 16);
+    const int wbuf = lds0 + tbytes + wave * (2 * kWinSetBytes);
+    const int op_lane = 32 * li + 16 * g;
     int v_lane;
     {
         const int li_hi = (lane >> 4) & 1, s = lane & 15, odd = s & 1, jj = s >> 1, aa = jj >> 2, bb = jj & 3;
@@ -125,21 +127,18 @@ __device__ __forceinline__ void win_body(const QflashKernelArgs& a) {
     }
     const size_t pair_bytes = (size_t)N * D;
 
-    v4i k_cur[2], q_cur, k_nxt[2] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}}, q_nxt = v4i{0, 0, 0, 0};
-    auto issue_loads = [&](const WinPair& q, int parity, v4i* kk, v4i& qq) {
+    auto issue_loads = [&](const WinPair& q, int parity) {
         const size_t off = (size_t)pair_index(q) * pair_bytes;
-        const int8_t* Kp = a.K + off;
-        const int8_t* Qp = a.Q + off;
-        kk[0] = *(const v4i*)(Kp + koff0);
-        kk[1] = *(const v4i*)(Kp + koff1);
-        qq = *(const v4i*)(Qp + qoff);
-        win_load_1k(a.V + off, voff0, vbuf + 2048 * parity);
-        win_load_1k(a.V + off, voff1, vbuf + 2048 * parity + 1024);
+        const int set = wbuf + kWinSetBytes * parity;
+        win_load_1k(a.K + off, voff0, set + 2048);
+        win_load_1k(a.Q + off, qoff, set + 4096);
+        win_load_1k(a.K + off, voff1, set + 3072);
+        win_load_1k(a.V + off, voff0, set);
+        win_load_1k(a.V + off, voff1, set + 1024);
     };
 
     // ---- accumulator input of the score product: bias (or 0) + 2^30, excluded / beyond the sequence: -2^29 + 2^30
     v16i cb[2];
-    int cur_slice = -1;
     auto load_slice = [&](int s_idx) {
         if (has_bias) {
             const int nb = (N + 31) / 32;                               // 2
@@ -159,105 +158,119 @@ __device__ __forceinline__ void win_body(const QflashKernelArgs& a) {
                 for (int v = 0; v < 16; ++v)
                     cb[kb][v] = (32 * kb + 8 * (v >> 2) + 4 * g + (v & 3) < N ? 0 : kWinExcluded) + kAccBias;
         }
-        cur_slice = s_idx;
     };
 
-    issue_loads(p, 0, k_cur, q_cur);
+    // ---- the run.  Loads of a pair are issued one pair ahead; the output of a pair is stored one
+    //      pair late, right after the only wait of the iteration, so that neither the loads nor the
+    //      store are waited for while they are young.  Pairs of one bias slice form the inner loop:
+    //      the accumulator input is invariant there.
+    issue_loads(p, 0);
     int parity = 0;
-    for (int t = t0; t < t1; ++t) {
-        if (p.s_idx != cur_slice) load_slice(p.s_idx);
-        const size_t o_off = (size_t)pair_index(p) * pair_bytes;
-        // everything in flight belongs to this pair (and to the stores of the previous one)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        WinPair pn = p;
-        advance(pn);
-        if (t + 1 < t1) issue_loads(pn, parity ^ 1, k_nxt, q_nxt);
+    v4i o_prev = v4i{0, 0, 0, 0};
+    size_t o_prev_off = 0;
+    bool have_prev = false;
+    const unsigned o_lane = (unsigned)(row * D + 16 * g);
+    int t = t0;
+    while (t < t1) {
+        load_slice(p.s_idx);
+        const int t_end = min(t1, t + (Rb - p.i) * Rh - p.j);       // pairs of this slice from here on
+        for (; t < t_end; ++t) {
+            // everything in flight belongs to this pair (or is the store of the one before the last)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const size_t o_off = (size_t)pair_index(p) * pair_bytes;
+            advance(p);
+            if (t + 1 < t1) issue_loads(p, parity ^ 1);
+            if (have_prev && row < N) *(v4i*)(a.O + o_prev_off + o_lane) = o_prev;
 
-        // ---- step 1: S^T + bias (two blocks of 32 keys x 32 queries)
-        v16i s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(k_cur[kb], q_cur, cb[kb], 0, 0, 0);
-        // ---- steps 2, 3: row maximum (unsigned: every value carries 2^30), never below the initial maximum
-        int m_new;
-        {
-            unsigned mk[2];
+            // ---- step 1: S^T + bias (two blocks of 32 keys x 32 queries)
+            const int set = wbuf + kWinSetBytes * parity;
+            const v4i q_cur = *(lds_v4i*)(size_t)(set + 4096 + op_lane);
+            v16i s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                mk[kb] = kb == 0 ? (unsigned)kMInit + (unsigned)kAccBias : 0u;
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    mk[kb] = max(max(mk[kb], (unsigned)s[kb][4 * a4]), (unsigned)s[kb][4 * a4 + 1]);
-                    mk[kb] = max(max(mk[kb], (unsigned)s[kb][4 * a4 + 2]), (unsigned)s[kb][4 * a4 + 3]);
-                }
+                const v4i k_cur = *(lds_v4i*)(size_t)(set + 2048 + 1024 * kb + op_lane);
+                s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(k_cur, q_cur, cb[kb], 0, 0, 0);
             }
-            const HalfPair hp = both_halves((int)max(mk[0], mk[1]));
-            m_new = (int)max((unsigned)hp.x, (unsigned)hp.y);
-        }
-        // ---- steps 5-7: weights, packed four to a dword (the B operand of the second product), row sum
-        v4i pk[2];
-        int rowsum = 0;
-        if (XM == kExpTable) {
-            const unsigned edge = (unsigned)m_new - (unsigned)to_vgpr(hc.lut_xp);
+            // ---- steps 2, 3: row maximum (unsigned: every value carries 2^30), never below the initial maximum
+            int m_new;
+            {
+                unsigned mk[2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < 2; ++kb) {
+                    mk[kb] = kb == 0 ? (unsigned)kMInit + (unsigned)kAccBias : 0u;
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    s[kb][v] = table_weight(__builtin_elementwise_sub_sat((unsigned)s[kb][v], edge));
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const unsigned w = pack_byte<0>((unsigned)s[kb][4 * a4], (unsigned)s[kb][4 * a4 + 1],
-                                                    (unsigned)s[kb][4 * a4 + 2], (unsigned)s[kb][4 * a4 + 3]);
-                    pk[kb][a4] = (int)w;
-                    rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
-                }
-        } else {
-            const int lo = m_new + c.x_floor;
-            const int m2 = m_new - 2 * c.s_inv;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    unsigned pr[4];
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int y = shift_exp2<KZ>(max(s[kb][4 * a4 + b], lo), m_new, m2, c);
-                        pr[b] = (unsigned)__mul24(y, c.p_mul_hi_v);
+                    for (int a4 = 0; a4 < 4; ++a4) {
+                        mk[kb] = max(max(mk[kb], (unsigned)s[kb][4 * a4]), (unsigned)s[kb][4 * a4 + 1]);
+                        mk[kb] = max(max(mk[kb], (unsigned)s[kb][4 * a4 + 2]), (unsigned)s[kb][4 * a4 + 3]);
                     }
-                    const unsigned w = pack_byte3(pr[0], pr[1], pr[2], pr[3]);
-                    pk[kb][a4] = (int)w;
-                    rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
                 }
-        }
-        RowState<D> st;
-        {
-            const HalfPair hp = both_halves(rowsum);
-            st.l = hp.x + hp.y;
-        }
-        st.m = m_new;
-        // ---- step 8: O^T = V^T P^T, the V^T operand read transposed from the row-major V in LDS
-        {
-            const int vb = vbuf + 2048 * parity + v_lane;
-            v16i acc = offset_block();
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const v2i_t lo2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(size_t)(vb + 1024 * kb));
-                const v2i_t hi2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(size_t)(vb + 1024 * kb + 512));
-                const v4i va = __builtin_shufflevector(lo2, hi2, 0, 1, 2, 3);
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], acc, 0, 0, 0);
+                const HalfPair hp = both_halves((int)max(mk[0], mk[1]));
+                m_new = (int)max((unsigned)hp.x, (unsigned)hp.y);
             }
-            st.acc[0] = acc;
+            // ---- steps 5-7: weights, packed four to a dword (the B operand of the second product), row sum
+            v4i pk[2];
+            int rowsum = 0;
+            if (XM == kExpTable) {
+                const unsigned edge = (unsigned)m_new - (unsigned)to_vgpr(hc.lut_xp);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        s[kb][v] = table_weight(__builtin_elementwise_sub_sat((unsigned)s[kb][v], edge));
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int a4 = 0; a4 < 4; ++a4) {
+                        const unsigned w = pack_byte<0>((unsigned)s[kb][4 * a4], (unsigned)s[kb][4 * a4 + 1],
+                                                        (unsigned)s[kb][4 * a4 + 2], (unsigned)s[kb][4 * a4 + 3]);
+                        pk[kb][a4] = (int)w;
+                        rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
+                    }
+            } else {
+                const int lo = m_new + c.x_floor;
+                const int m2 = m_new - 2 * c.s_inv;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int a4 = 0; a4 < 4; ++a4) {
+                        unsigned pr[4];
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const int y = shift_exp2<KZ>(max(s[kb][4 * a4 + b], lo), m_new, m2, c);
+                            pr[b] = (unsigned)__mul24(y, c.p_mul_hi_v);
+                        }
+                        const unsigned w = pack_byte3(pr[0], pr[1], pr[2], pr[3]);
+                        pk[kb][a4] = (int)w;
+                        rowsum = __builtin_amdgcn_sdot4((int)w, 0x01010101, rowsum, false);
+                    }
+            }
+            RowState<D> st;
+            {
+                const HalfPair hp = both_halves(rowsum);
+                st.l = hp.x + hp.y;
+            }
+            st.m = m_new;
+            // ---- step 8: O^T = V^T P^T, the V^T operand read transposed from the row-major V in LDS
+            {
+                const int vb = set + v_lane;
+                v16i acc = offset_block();
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const v2i_t lo2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(size_t)(vb + 1024 * kb));
+                    const v2i_t hi2 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(size_t)(vb + 1024 * kb + 512));
+                    const v4i va = __builtin_shufflevector(lo2, hi2, 0, 1, 2, 3);
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(va, pk[kb], acc, 0, 0, 0);
+                }
+                st.acc[0] = acc;
+            }
+            // ---- step 11; the store follows in the next iteration
+            normalise_words<D, 16>(st, a.out_round != 0, &o_prev);
+            o_prev_off = o_off;
+            have_prev = true;
+            parity ^= 1;
         }
-        // ---- step 11 and the store
-        if (row < N) normalise_store<D, 16>(st, a.O + o_off + (size_t)row * D, g, a.out_round != 0);
-
-        p = pn;
-        parity ^= 1;
-        k_cur[0] = k_nxt[0];
-        k_cur[1] = k_nxt[1];
-        q_cur = q_nxt;
     }
+    if (have_prev && row < N) *(v4i*)(a.O + o_prev_off + o_lane) = o_prev;
 }
 
 template <int XM>
