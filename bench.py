@@ -38,7 +38,7 @@ CUS, LANES_PER_CU_CLK, CLOCK_GHZ = 256, 64, 2.4
 PEAK_ALU_TOPS = CUS * LANES_PER_CU_CLK * CLOCK_GHZ / 1000.0    # 39.3 T integer lane-ops/s
 ALU_OPS_PER_SCORE = 14.0         # algorithmic integer lane-operations per score element (the paper's steps)
 LLC_BYTES = 256 << 20
-KERNEL_SOURCES = ["qflash_kernels.hip", "qflash_resident.h", "qflash_cu.hip", "qflash_win.hip", "qflash_qmax.hip",
+KERNEL_SOURCES = ["qflash_kernels.hip", "qflash_resident.h", "qflash_cu.hip", "qflash_win.hip", "qflash_ring.hip", "qflash_qmax.hip",
                   "qflash_tile.h", "qflash_device.h", "qflash_internal.h", "qflash_dynamic.hip", "qflash_api.cpp",
                   "qflash_plan.cpp", "qflash_derive.h"]
 

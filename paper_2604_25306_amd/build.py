@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqflash.so")
-SOURCES = ["qflash_api.cpp", "qflash_plan.cpp", "qflash_kernels.hip", "qflash_qmax.hip", "qflash_cu.hip", "qflash_win.hip", "qflash_dynamic.hip", "qflash_peaks.hip"]
+SOURCES = ["qflash_api.cpp", "qflash_plan.cpp", "qflash_kernels.hip", "qflash_qmax.hip", "qflash_cu.hip", "qflash_win.hip", "qflash_ring.hip", "qflash_dynamic.hip", "qflash_peaks.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

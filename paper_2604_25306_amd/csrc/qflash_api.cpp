@@ -162,6 +162,17 @@ extern "C" void qflash_debug_trace(void* buf) { g_trace = (unsigned long long*)b
 
 namespace {
 
+// The kernel family the plan chose.
+int launch_attention(QflashKernelArgs& a, int d, int kv_tile, int lds_limit, void* hip_stream) {
+    if (a.win_mode) return qflash_launch_fwd_win(a, lds_limit, hip_stream);
+    if (a.cu_mode) return qflash_launch_fwd_cu(a, lds_limit, hip_stream);
+    if (a.ring_dma) {
+        a.ring_table_lds = (a.lut_bytes_max + 1023) & ~1023;
+        return qflash_launch_fwd_ring(a, lds_limit, hip_stream);
+    }
+    return qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+}
+
 // Whether the planned launch can hold a weight table of table_bytes in LDS and copying it pays.
 bool table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds_limit) {
     if (a.win_mode) return table_bytes <= a.win_table_lds;      // staged once per compute unit
@@ -237,6 +248,7 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
     a.exp_mode = all_k0 ? 1 : 0;
     a.lut_bytes_max = 0;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
+    a.ring_table_lds = 0;
     // The kernel that gives a whole compute unit to one workgroup, where the shape allows it: its LDS
     // budget depends on the size of the weight table the call would use.
     {
@@ -388,19 +400,15 @@ int attention_impl(qflash_ctx* ctx, const int8_t* Q, const int8_t* K, const int8
         } else {
             for (int h = 0; h < n_p; ++h) { a.hc[h].lut = nullptr; a.hc[h].lut_bytes = 0; a.hc[h].lut_xp = 0; }
         }
-        if (rc == 0) rc = a.win_mode  ? qflash_launch_fwd_win(a, lds_limit, hip_stream)
-                          : a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream)
-                                      : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+        if (rc == 0) rc = launch_attention(a, d, kv_tile, lds_limit, hip_stream);
         ctx->last_mode = a.exp_mode == 2 ? QFLASH_WEIGHTS_TABLE : a.exp_mode == 3 ? QFLASH_WEIGHTS_MIXED : QFLASH_WEIGHTS_ARITHMETIC;
-        ctx->last_kernel = a.win_mode ? 4 : a.cu_mode ? 3 : !a.resident ? 0 : a.ring ? 2 : 1;
+        ctx->last_kernel = a.win_mode ? 4 : a.cu_mode ? 3 : !a.resident ? 0 : a.ring ? 2 : 1;   // (2 also for the direct-load ring)
         lk.unlock();
         if (cur != device) (void)hipSetDevice(cur);
         if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
         return QFLASH_OK;
     }
-    if (rc == 0) rc = a.win_mode  ? qflash_launch_fwd_win(a, lds_limit, hip_stream)
-                          : a.cu_mode ? qflash_launch_fwd_cu(a, lds_limit, hip_stream)
-                                      : qflash_launch_fwd(a, d, kv_tile, lds_limit, hip_stream);
+    if (rc == 0) rc = launch_attention(a, d, kv_tile, lds_limit, hip_stream);
     if (cur != device) (void)hipSetDevice(cur);
     if (rc != 0) { (void)hipGetLastError(); return QFLASH_ERR_LAUNCH; }
     return QFLASH_OK;
@@ -457,6 +465,7 @@ extern "C" int qflash_plan_query(qflash_ctx* ctx, int B, int H, int N, int d, in
     a.bias_H = has_bias ? bias_H : 1;
     a.B = B; a.H = H; a.N = N;
     a.n_cu = n_cu;
+    a.qmax = qmax ? 1 : 0;
     if (qflash_plan_fwd(B * H, N, d, kv_tile, lds_limit, &a) != 0) return QFLASH_ERR_SHAPE;
     std::memset(out, 0, sizeof *out);
     a.bias_packed = has_bias ? 1 : 0;      // (a bias is taken to be in the packed layout, the only one kernel 4 reads)

@@ -73,17 +73,27 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     a->heads_per_wg = 1;
     a->pipelined = 0;
     a->ring = 0;
+    a->ring_dma = 0;
     a->kv_tile = kv_tile;
     // Long sequences: K and V^T of the whole sequence (plus a weight table) would leave room for
     // one workgroup per compute unit, or for none.  Where the kernel variant can stage tile by
     // tile (d = 64, tile 64), LDS holds two tiles only and workgroups are at most 8 wavefronts,
     // so that two of them share a compute unit.
     const bool two_fit = qflash_resident_lds_bytes(N, d, 1, kRingTableGuess, lds_limit / 2) != 0;
-    if (d == 64 && N > 256 && (kv_tile == 128 || !two_fit)) {
+    // (without a bias the ring fed by direct loads is the faster kernel for every long sequence)
+    if (d == 64 && N > 256 && (kv_tile == 128 || !two_fit || (!a->bias && !a->qmax))) {
         const int nblk = (N + 31) / 32;
         const int cus = a->n_cu > 0 ? a->n_cu : 256;
         int waves;
-        if (kv_tile == 128) {
+        // Without a bias the ring is fed by direct global-to-LDS loads (qflash_fwd_ring): no wavefront
+        // stages anything, registers allow five (tile 64) or three (tile 128) wavefronts per SIMD, and
+        // workgroups of four wavefronts, one per SIMD, measured best (DeiT-B/384: 45.3 us against
+        // 50.9 with seven or eight and 54.6 with five or six).
+        a->ring_dma = (!a->bias && !a->qmax) ? 1 : 0;
+        if (a->ring_dma) {
+            const int tiles = (nblk + 3) / 4;
+            waves = (nblk + tiles - 1) / tiles;                   // balanced: at most 4
+        } else if (kv_tile == 128) {
             // 160-odd registers leave three wavefront slots per SIMD: three workgroups of four
             // wavefronts (which is also what stages a tile: 256 threads, two items each)
             waves = 4;
@@ -155,6 +165,7 @@ int qflash_table_fits(const QflashKernelArgs& a, int d, int table_bytes, int lds
     // the bytes of Q, K, V, O the workgroup moves anyway.
     const long long io = 4ll * a.heads_per_wg * a.N * d;
     if (io < (long long)table_bytes) return 0;
+    if (a.ring_dma) return qflash_ring_lds_bytes(a.waves_per_head, a.kv_tile, table_bytes) <= (size_t)lds_limit / 2;
     // Short sequences with the wide tile: that variant is out of registers with the table's
     // addressing on top (ViT-B/16 B=64: 34 us with the table, 25.5 us without).
     if (d == 64 && a.kv_tile == 128 && a.N <= 256) return 0;
@@ -187,6 +198,12 @@ int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_b
     a->cu_waves = units < 16 ? units : 16;
     a->cu_table_lds = (table_bytes + 1023) & ~1023;
     return 1;
+}
+
+// LDS bytes of the direct-load ring kernel: table (rounded up to 1 KiB), 2 KiB of query rows per
+// wavefront, two KV tiles (K and V, 64-byte rows).
+size_t qflash_ring_lds_bytes(int waves, int kv_tile, int table_bytes) {
+    return (((size_t)table_bytes + 1023) & ~(size_t)1023) + (size_t)waves * 2048 + 2 * (size_t)kv_tile * 128;
 }
 
 // LDS bytes of the windowed-attention kernel: the table (rounded up to 1 KiB) and, per wavefront

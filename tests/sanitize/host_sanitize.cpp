@@ -3,8 +3,8 @@
 // -fsanitize=address,undefined.  Built and run by tests/test_sanitizers.py:
 //
 //   gcc -std=c11 -O1 -g -fsanitize=address,undefined -fno-sanitize-recover=all -fopenmp -c oracle/qflash_oracle.c
-//   g++ -std=c++17 -O1 -g -fsanitize=address,undefined -fno-sanitize-recover=all -fopenmp \
-//       -I include -I paper_2604_25306_amd/csrc tests/sanitize/host_sanitize.cpp \
+//   g++ -std=c++17 -O1 -g -fsanitize=address,undefined -fno-sanitize-recover=all -fopenmp
+//       -I include -I paper_2604_25306_amd/csrc tests/sanitize/host_sanitize.cpp
 //       paper_2604_25306_amd/csrc/qflash_plan.cpp qflash_oracle.o -o host_sanitize && ./host_sanitize
 //
 // Every check is an invariant the code under test must keep for any input; a sanitizer report or a
@@ -172,10 +172,13 @@ static void kernel_plans() {
         CHECK(a.heads_per_wg >= 1 && a.heads_per_wg * a.waves_per_head <= kResidentMaxWavesWide);
         CHECK(a.rows_per_wg == 32 * a.waves_per_head && (long long)a.rows_per_wg * a.n_qtiles >= N);
         CHECK(a.heads_per_wg == 1 || a.n_qtiles == 1);
-        CHECK(!a.ring || (a.pipelined && d == 64 && a.heads_per_wg == 1 && a.waves_per_head >= 4));
-        CHECK(!a.pipelined || (a.resident && a.waves_per_head >= 4 && N > tile));
+        CHECK(!a.ring || (a.pipelined && d == 64 && a.heads_per_wg == 1 && (a.waves_per_head >= 4 || a.ring_dma)));
+        CHECK(!a.ring_dma || (a.ring && !a.bias && a.waves_per_head <= 4 &&
+                              qflash_ring_lds_bytes(a.waves_per_head, tile, 40 * 1024) <= (size_t)lds));
+        CHECK(!a.pipelined || (a.resident && (a.waves_per_head >= 4 || a.ring_dma) && N > tile));
         if (a.resident) {
-            const size_t bytes = qflash_resident_lds_bytes(N, d, a.heads_per_wg, 0, lds, a.ring ? tile : 0);
+            const size_t bytes = a.ring_dma ? qflash_ring_lds_bytes(a.waves_per_head, tile, 0)
+                                            : qflash_resident_lds_bytes(N, d, a.heads_per_wg, 0, lds, a.ring ? tile : 0);
             CHECK(bytes > 0 && bytes <= (size_t)lds);
         }
         const long long pairs = (long long)B * H;

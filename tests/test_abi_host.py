@@ -168,10 +168,14 @@ def test_plan_of_the_benchmark_shapes(lib):
     assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.units, p.query_blocks) == (3, 3, 16, 256, 7)
     p = qf.qflash_plan_query(None, 1024, 6, 197, 64, 64)     # too many pairs for one round: a workgroup per pair
     assert (p.kernel, p.wavefronts_per_pair, p.units, p.tile_by_tile) == (1, 7, 6144, 1)
-    p = qf.qflash_plan_query(None, 32, 12, 577, 64, 64)        # two-tile ring, 4 wavefronts: fewer turns per CU
+    p = qf.qflash_plan_query(None, 32, 12, 577, 64, 64)        # two-tile ring fed by direct loads: 4 wavefronts per workgroup
     assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 4, 5)
-    p = qf.qflash_plan_query(None, 16, 16, 577, 64, 64)        # same turns either way: the larger workgroup
-    assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 7, 3)
+    p = qf.qflash_plan_query(None, 16, 16, 577, 64, 128)
+    assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 4, 5)
+    p = qf.qflash_plan_query(None, 16, 16, 577, 64, 64, 16, 16)  # with a bias: the ring staged by the wavefronts; same turns
+    assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 7, 3)   # either way, so the larger workgroup
+    p = qf.qflash_plan_query(None, 4, 4, 300, 64, 64)          # every long sequence without a bias takes the ring
+    assert (p.kernel, p.wavefronts_per_pair, p.query_blocks) == (2, 4, 3)
     p = qf.qflash_plan_query(None, 4096, 3, 49, 32, 64, 64, 3)  # windowed: 256 persistent workgroups, 8 runs of 6 pairs each
     assert (p.kernel, p.pairs_per_workgroup, p.wavefronts_per_pair, p.workgroups) == (4, 48, 2, 256)
     p = qf.qflash_plan_query(None, 4097, 3, 49, 32, 64, 64, 3)  # the bias extents do not divide the batch: the resident kernel,
