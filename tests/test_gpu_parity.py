@@ -325,6 +325,83 @@ def test_whole_compute_unit_kernel(gpu, bhn):
         check(gpu, Q, K, V, p2, 64, label="whole CU, x_shift %d" % p2.x_shift)
 
 
+# (B, H, N, bias_B, bias_H, tile): runs that end inside a slice, slices that change inside a run, more
+# heads than bias heads, one bias for everything, fewer pairs than compute units, no bias at all
+WINDOWED_SHAPES = [(4096 // 16, 3, 49, 64, 3, 64), (70, 3, 49, 10, 3, 64), (2315, 1, 49, 5, 1, 64), (36, 6, 49, 12, 2, 128),
+                   (1000, 3, 33, 1, 1, 64), (64, 4, 64, 64, 4, 64), (9, 24, 49, 1, 24, 64), (2, 2, 40, 2, 1, 64),
+                   (700, 3, 49, 0, 0, 64), (3, 5, 57, 0, 0, 128), (1, 1, 63, 1, 1, 64)]
+
+
+@pytest.mark.parametrize("shape", WINDOWED_SHAPES)
+def test_windowed_kernel(gpu, shape):
+    """Windows of 33 to 64 tokens with 32 features: the persistent kernel in which every wavefront
+    works through a run of pairs of one bias slice with the bias in registers.  The packed-bias
+    call (and the call without a bias) must take it, the plain-bias call the resident kernel; all
+    three equal the oracle."""
+    torch, qf, ctx = gpu
+    B, H, N, bB, bH, tile = shape
+    Q, K, V, sQ, sK, _ = rand_case((B, H, N, 32), 1300 + B + N, q_gain=1.0 + (N % 3) * 0.3)
+    rng = np.random.default_rng(B + N)
+    bias = None
+    if bB:
+        bias = rng.integers(-2500, 2500, size=(bB, bH, N, N)).astype(np.int32)
+        bias[rng.random(bias.shape) < 0.25] = EXCLUDED
+        bias[..., 0] = 17                       # every row keeps a key ...
+        bias[0, 0, N // 2, :] = EXCLUDED        # ... but one, which is excluded altogether
+    for out_round in ((0, 1) if N == 49 and B < 100 else (0,)):
+        p = oracle.derive_params(sQ, sK, 32, out_round=out_round)
+        ref = oracle.qflash_attention(Q, K, V, p, tile, bias=bias)
+        out = run_gpu(gpu, Q, K, V, p, tile, bias=bias, packed=bias is not None)
+        assert qf.qflash_cache_query(ctx.handle).last_kernel == 4, shape
+        assert_same(out, ref, "windowed %s" % (shape,))
+        if bias is not None and B * H <= 1000:
+            out = run_gpu(gpu, Q, K, V, p, tile, bias=bias, packed=False)
+            assert qf.qflash_cache_query(ctx.handle).last_kernel == 1, shape
+            assert_same(out, ref, "windowed, plain bias %s" % (shape,))
+    # coarse scores (x_shift > 0): the arithmetic variant with the left shift
+    if N in (49, 40):
+        p2 = oracle.derive_params(sQ * 40.0, sK * 40.0, 32)
+        assert p2.x_shift > 0
+        b2 = None if bias is None else np.where(bias == EXCLUDED, bias, bias // 1500).astype(np.int32)
+        assert_same(run_gpu(gpu, Q, K, V, p2, tile, bias=b2, packed=b2 is not None),
+                    oracle.qflash_attention(Q, K, V, p2, tile, bias=b2), "windowed, x_shift %d" % p2.x_shift)
+
+
+def test_windowed_kernel_is_not_taken_when_the_bias_does_not_divide_the_batch(gpu):
+    torch, qf, ctx = gpu
+    Q, K, V, sQ, sK, _ = rand_case((7, 3, 49, 32), 1401)
+    p = oracle.derive_params(sQ, sK, 32)
+    bias = np.random.default_rng(1).integers(-2000, 2000, size=(2, 3, 49, 49)).astype(np.int32)
+    out = run_gpu(gpu, Q, K, V, p, 64, bias=bias, packed=True)
+    assert qf.qflash_cache_query(ctx.handle).last_kernel == 1
+    assert_same(out, oracle.qflash_attention(Q, K, V, p, 64, bias=bias), "7 images, 2 bias slices")
+
+
+# long sequences without a bias: the two-tile ring fed by direct loads, both tile sizes, ragged last tiles,
+# one to five row blocks in the last workgroup of a pair, fewer than four wavefronts per workgroup
+DIRECT_RING_SHAPES = [(2, 3, 257, 64), (3, 2, 288, 128), (1, 5, 320, 64), (2, 2, 383, 128), (1, 3, 449, 64),
+                      (4, 12, 577, 64), (4, 12, 577, 128), (1, 2, 640, 64), (1, 1, 1030, 128), (1, 2, 2049, 64),
+                      (1, 1, 4096, 64)]
+
+
+@pytest.mark.parametrize("shape", DIRECT_RING_SHAPES)
+def test_direct_load_ring(gpu, shape):
+    torch, qf, ctx = gpu
+    B, H, N, tile = shape
+    plan = qf.qflash_plan_query(ctx.handle, B, H, N, 64, tile)
+    assert plan.kernel == 2 and plan.wavefronts_per_pair <= 4, (shape, plan.kernel, plan.wavefronts_per_pair)
+    Q, K, V, sQ, sK, _ = rand_case((B, H, N, 64), 1500 + N, sigma=1.0 + (N % 2) * 0.5)
+    p = oracle.derive_params(sQ, sK, 64, out_round=N % 2)
+    check(gpu, Q, K, V, p, tile, label="direct ring %s" % (shape,))
+    if N in (257, 577):
+        # per-head constants (tables of different sizes, one head coarse), and a late outlier key
+        ps = [oracle.derive_params(sQ * gq, sK, 64) for gq in ([1.0, 0.5, 40.0] + [1.3] * H)[:H]]
+        check(gpu, Q, K, V, ps, tile, label="direct ring per head %s" % (shape,))
+        K2 = K.copy()
+        K2[:, :, N - 3] = np.sign(Q[:, :, 5]) * 127
+        check(gpu, Q, K2, V, p, tile, label="direct ring, late outlier %s" % (shape,))
+
+
 @pytest.mark.parametrize("tile", [64, 128])
 def test_streamed_kernel_with_bias(gpu, tile):
     """d = 32 and a sequence too long for LDS: the kernel that streams KV tiles, with a bias in both
