@@ -139,7 +139,7 @@ int qflash_cache_query(qflash_ctx* ctx, qflash_cache_info* out /* host */);
  *            sequences (N <= 256) tile 128 takes 1.2 to 1.3 times the time of tile 64 (ViT-B/16
  *            B=64: 25.5 against 21.4 us; the variant runs short of registers, and the library
  *            computes its weights arithmetically there because the look-up variant is slower
- *            still); on long sequences with d = 64 it is 5 % faster (N = 577).  A d = 32 sequence
+ *            still); on long sequences with d = 64 it is 4 % faster (N = 577: 44.3 against 46.2 us).  A d = 32 sequence
  *            too long for LDS (N above about 1000) takes the streamed kernel, which stages one
  *            tile at a time with two barriers per tile and computes weights arithmetically:
  *            about 0.8 of the ring kernel's rate per score with tile 64 (B*H = 64, N = 2100:
@@ -313,7 +313,9 @@ int qflash_attention_dynamic_bias(qflash_ctx* ctx,
  *
  *   bias_B, bias_H   extents of the bias the call would be given, or 0, 0 for none.
  *   kernel           0: KV tiles streamed through LDS, 128 query rows per workgroup;
- *                    1: K and V of a (batch, head) pair resident in LDS; 2: two KV tiles in LDS;
+ *                    1: K and V of a (batch, head) pair resident in LDS; 2: two KV tiles in LDS (long
+ *                    sequences with d = 64; without a bias they are fed by direct global-to-LDS loads and
+ *                    workgroups are four wavefronts);
  *                    3: one workgroup per compute unit holds Q, K, V of several pairs in LDS (short
  *                    sequences, d = 64, kv_tile 64, no bias, one set of constants, few enough pairs for
  *                    a single round of workgroups; assumes a weight table of 32 KiB).  For kernel 3:

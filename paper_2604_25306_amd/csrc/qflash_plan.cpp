@@ -200,10 +200,11 @@ int qflash_plan_cu(int BH, int N, int d, int kv_tile, int lds_limit, int table_b
     return 1;
 }
 
-// LDS bytes of the direct-load ring kernel: table (rounded up to 1 KiB), 2 KiB of query rows per
-// wavefront, two KV tiles (K and V, 64-byte rows).
+// LDS bytes of the direct-load ring kernel: table (rounded up to 1 KiB) and two KV tiles (K and V,
+// 64-byte rows).
 size_t qflash_ring_lds_bytes(int waves, int kv_tile, int table_bytes) {
-    return (((size_t)table_bytes + 1023) & ~(size_t)1023) + (size_t)waves * 2048 + 2 * (size_t)kv_tile * 128;
+    (void)waves;
+    return (((size_t)table_bytes + 1023) & ~(size_t)1023) + 2 * (size_t)kv_tile * 128;
 }
 
 // LDS bytes of the windowed-attention kernel: the table (rounded up to 1 KiB) and, per wavefront

@@ -3,8 +3,7 @@
 // global-to-LDS loads.
 //
 // A workgroup of up to 8 wavefronts (4 where the sequence allows it) serves 32 query rows per wavefront of one (batch, head) pair and
-// walks over all KV tiles of the pair.  LDS holds the weight table, the wavefronts' query rows and
-// two KV tiles: the one in use and the one on its way.  K and V tiles arrive row-major as they lie
+// walks over all KV tiles of the pair.  LDS holds the weight table and two KV tiles: the one in use and the one on its way.  K and V tiles arrive row-major as they lie
 // in memory (64-byte rows, 16-byte pieces permuted by the row so that operand reads are free of bank
 // conflicts), put there by `global_load_lds_dwordx4`; the K/Q operands are plain 16-byte LDS reads
 // and the V^T operand is read with the transposing 8-bit LDS read (see qflash_tile.h).  Compared with
@@ -59,12 +58,11 @@ __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
     const ExpConst c = make_exp_const(hc);
     const SwizzledLane sl = swizzled_lane_offsets(lane);
 
-    // ---- LDS: [weight table][wavefront w: its 32 query rows, 2 KiB][slot 0][slot 1]; the dynamic LDS
-    //      is the only LDS of the kernel, so the table index is its address
+    // ---- LDS: [weight table][slot 0][slot 1]; the dynamic LDS is the only LDS of the kernel, so the
+    //      table index is its address
     const int lds0 = (int)(size_t)(lds_void_r)smem_ring;
     const int tbytes = XM == kExpTable ? a.ring_table_lds : 0;
-    const int q_base = lds0 + tbytes + 2048 * wave;
-    const int ring_base = lds0 + tbytes + 2048 * n_waves;
+    const int ring_base = lds0 + tbytes;
 
     const size_t head_off = (size_t)bh * N * D;
     const int8_t* Kh = a.K + head_off;
@@ -86,26 +84,29 @@ __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
         }
     };
 
-    // ---- prologue: table (shared), own query rows, first tile; one wait, one barrier
+    // ---- prologue: table (shared), first tile, this lane's query row (straight to its operand
+    //      registers; rows beyond the sequence read the last row and are never stored); one wait,
+    //      one barrier.  The query registers are touched right after the wait: these are the only
+    //      loads the compiler counts, and it must not find them pending later, when waiting for
+    //      them would mean waiting for the tile in flight.
     if (XM == kExpTable)
         for (int it = wave; it < (tbytes >> 10); it += n_waves)
             ring_load_1k((const int8_t*)hc.lut + 1024 * it, 16 * lane, lds0 + 1024 * it);
-    {
-        const int8_t* Qh = a.Q + head_off;
-        const int r = min(row0, N - 1);            // (a wavefront without rows loads something valid and never uses it)
-        ring_load_1k(Qh, block_off(r), q_base);
-        ring_load_1k(Qh, block_off(r + 16), q_base + 1024);
-    }
     issue_tile(0);
+    v4i qreg[2];
+    {
+        const int8_t* Qrow = a.Q + head_off + (size_t)min(row0 + li, N - 1) * D + 16 * g;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) qreg[s] = *(const v4i*)(Qrow + 32 * s);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int s = 0; s < 2; ++s) asm volatile("" : "+v"(qreg[s]));
     __syncthreads();
 
     RowState<D> st;
     st.l = 0;
     st.m = SB ? (int)((unsigned)kMInit + (unsigned)kAccBias) : kMInit;
-    v4i qreg[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) qreg[s] = *(lds_v4i*)(size_t)(q_base + (sl.k_off ^ (32 * s)));
 
     const int n_full = N / BC, rem = N - n_full * BC;
 #define QF_RING_TILE(FULL_, FIRST_, J_, NV_)                                                                   \
@@ -135,9 +136,11 @@ __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
     normalise_store<D, 20>(st, a.O + head_off + (size_t)i * D, g, a.out_round != 0);
 }
 
-// Wavefronts per SIMD the register allocation has to allow: 5 with KV tiles of 64 (96 registers), 3 with 128.
+// Wavefronts per SIMD the register allocation has to allow: with KV tiles of 64, 5 for the look-up
+// variant (94 registers) and 4 for the others (which would spill at 96); 3 with tiles of 128 (137
+// registers; held to 128 it spills a dozen and is a sixth slower).
 template <int BC, int XM>
-__global__ __launch_bounds__(512, (BC == 64 ? 5 : 3)) void qflash_fwd_ring(const QflashKernelArgs a) {
+__global__ __launch_bounds__(512, (BC == 128 ? 3 : XM == kExpTable ? 5 : 4)) void qflash_fwd_ring(const QflashKernelArgs a) {
     if constexpr (XM == kExpAuto) {
         const int unit = qflash_unit_of_workgroup(blockIdx.x, a.units_per_xcd, a.xcd_period);
         if (unit >= a.n_units) return;
