@@ -52,7 +52,7 @@ struct QflashKernelArgs {
     int cu_groups;           // workgroups
     int cu_waves;            // wavefronts per workgroup (at most 16)
     int cu_table_lds;        // LDS bytes reserved for the weight table (a multiple of 1 KiB)
-    // two-tile ring fed by direct global-to-LDS loads (d = 64, no bias; set by qflash_plan_fwd, which reads qmax): 1 if the launch takes it
+    // two-tile ring fed by direct global-to-LDS loads (d = 64, no bias; set by qflash_plan_fwd): 1 if the launch takes it
     int ring_dma;
     int ring_table_lds;      // LDS bytes reserved for the weight table (a multiple of 1 KiB)
     // windowed-attention kernel (qflash_plan_win): 1 if the launch takes it
@@ -114,7 +114,7 @@ int qflash_launch_fwd(const QflashKernelArgs& args, int d, int kv_tile, int lds_
 int qflash_launch_fwd_qmax(const QflashKernelArgs& args, int d, int kv_tile, size_t lds_bytes, int lds_limit, int threads, void* stream);
 
 // Choose the kernel variant for BH heads of N rows and fill the work decomposition fields
-// (resident, pipelined, ring, ring_dma, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd, xcd_period, same_head; reads bias, bias_B, B, H, per_head, qmax).
+// (resident, pipelined, ring, ring_dma, rows_per_wg, waves_per_head, heads_per_wg, n_qtiles, n_units, units_per_xcd, xcd_period, same_head; reads bias, bias_B, B, H, per_head).
 // Returns non-zero if the launch would be too large.
 // lds_limit = LDS bytes one workgroup may use on this device.
 int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKernelArgs* args);   // n_cu is the caller's
@@ -133,8 +133,8 @@ int qflash_plan_win(int d, int kv_tile, int lds_limit, int table_bytes, QflashKe
 int qflash_launch_fwd_win(const QflashKernelArgs& args, int lds_limit, void* stream);
 size_t qflash_win_lds_bytes(int streams, int table_bytes);
 
-// The two-tile ring with direct global-to-LDS loads (long sequences, d = 64, no bias, Algorithm 1
-// only; work decomposition as for the ring of the resident kernel, four wavefronts per workgroup).
+// The two-tile ring with direct global-to-LDS loads (long sequences, d = 64, no bias, both
+// Algorithm 1 and the quantised-maximum variant; work decomposition as for the ring of the resident kernel, four wavefronts per workgroup).
 int qflash_launch_fwd_ring(const QflashKernelArgs& args, int lds_limit, void* stream);
 size_t qflash_ring_lds_bytes(int waves, int kv_tile, int table_bytes);
 

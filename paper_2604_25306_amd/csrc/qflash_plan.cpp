@@ -81,7 +81,7 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
     // so that two of them share a compute unit.
     const bool two_fit = qflash_resident_lds_bytes(N, d, 1, kRingTableGuess, lds_limit / 2) != 0;
     // (without a bias the ring fed by direct loads is the faster kernel for every long sequence)
-    if (d == 64 && N > 256 && (kv_tile == 128 || !two_fit || (!a->bias && !a->qmax))) {
+    if (d == 64 && N > 256 && (kv_tile == 128 || !two_fit || !a->bias)) {
         const int nblk = (N + 31) / 32;
         const int cus = a->n_cu > 0 ? a->n_cu : 256;
         int waves;
@@ -89,7 +89,7 @@ int qflash_plan_fwd(int BH, int N, int d, int kv_tile, int lds_limit, QflashKern
         // stages anything, registers allow five (tile 64) or three (tile 128) wavefronts per SIMD, and
         // workgroups of four wavefronts, one per SIMD, measured best (DeiT-B/384: 45.3 us against
         // 50.9 with seven or eight and 54.6 with five or six).
-        a->ring_dma = (!a->bias && !a->qmax) ? 1 : 0;
+        a->ring_dma = !a->bias ? 1 : 0;
         if (a->ring_dma) {
             const int tiles = (nblk + 3) / 4;
             waves = (nblk + tiles - 1) / tiles;                   // balanced: at most 4

@@ -40,7 +40,7 @@ __device__ __forceinline__ void ring_load_1k(const int8_t* g /* uniform */, int 
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_off), "s"((glb_void_r)g) : "memory", "m0");
 }
 
-template <int BC, int XM>
+template <int BC, int XM, bool QMAX>
 __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
     constexpr int D = 64;
     constexpr int kRingTileBytes = 2 * BC * D;      // one KV tile in LDS: K (BC rows x 64 bytes), then V
@@ -106,7 +106,8 @@ __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
 
     RowState<D> st;
     st.l = 0;
-    st.m = SB ? (int)((unsigned)kMInit + (unsigned)kAccBias) : kMInit;
+    const int m_init = QMAX ? qmax_initial_reference(hc.s_inv, hc.a_mul) : kMInit;
+    st.m = SB ? (int)((unsigned)m_init + (unsigned)kAccBias) : m_init;
 
     const int n_full = N / BC, rem = N - n_full * BC;
 #define QF_RING_TILE(FULL_, FIRST_, J_, NV_)                                                                   \
@@ -114,7 +115,7 @@ __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
         if ((J_) + 1 < n_tiles) issue_tile((J_) + 1);                                                          \
         if (active) {                                                                                          \
             const int slot = ring_base + kRingTileBytes * ((J_) & 1);                                          \
-            process_tile<D, BC, kBiasNone, XM, SB, FULL_, FIRST_, kLaySwizzled, 0>(                            \
+            process_tile<D, BC, kBiasNone, XM, SB, FULL_, FIRST_, kLaySwizzled, 0, QMAX>(                            \
                 st, qreg, nullptr, 0, nullptr, 0, NV_, hc.lut_xp, nullptr, nullptr, c, hc.a_mul, li, g,       \
                 slot + sl.k_off, slot + BC * D + sl.v_off);                                                      \
         }                                                                                                      \
@@ -139,21 +140,22 @@ __device__ __forceinline__ void ring_body(const QflashKernelArgs& a) {
 // Wavefronts per SIMD the register allocation has to allow: with KV tiles of 64, 5 for the look-up
 // variant (94 registers) and 4 for the others (which would spill at 96); 3 with tiles of 128 (137
 // registers; held to 128 it spills a dozen and is a sixth slower).
-template <int BC, int XM>
+// QMAX: the quantised-maximum variant (not Algorithm 1 as printed; see process_tile).
+template <int BC, int XM, bool QMAX>
 __global__ __launch_bounds__(512, (BC == 128 ? 3 : XM == kExpTable ? 5 : 4)) void qflash_fwd_ring(const QflashKernelArgs a) {
     if constexpr (XM == kExpAuto) {
         const int unit = qflash_unit_of_workgroup(blockIdx.x, a.units_per_xcd, a.xcd_period);
         if (unit >= a.n_units) return;
-        if (head_consts(a, unit / a.n_qtiles).lut_bytes > 0) ring_body<BC, kExpTable>(a);
-        else ring_body<BC, kExpShift>(a);
+        if (head_consts(a, unit / a.n_qtiles).lut_bytes > 0) ring_body<BC, kExpTable, QMAX>(a);
+        else ring_body<BC, kExpShift, QMAX>(a);
     } else {
-        ring_body<BC, XM>(a);
+        ring_body<BC, XM, QMAX>(a);
     }
 }
 
-template <int BC, int XM>
+template <int BC, int XM, bool QMAX>
 int launch_ring(const QflashKernelArgs& a, size_t lds, int lds_limit, hipStream_t st) {
-    auto kern = qflash_fwd_ring<BC, XM>;
+    auto kern = qflash_fwd_ring<BC, XM, QMAX>;
     // once per process and device: raise the dynamic LDS limit, and make sure that the kernel has no
     // static LDS in front of the dynamic one (the table index is used as an LDS address)
     static std::once_flag once[kQflashMaxDevices];
@@ -174,10 +176,26 @@ int launch_ring(const QflashKernelArgs& a, size_t lds, int lds_limit, hipStream_
 
 }  // namespace
 
+namespace {
+template <bool QMAX>
+int launch_variant(const QflashKernelArgs& a, size_t lds, int lds_limit, hipStream_t st) {
+    if (a.kv_tile == 64) {
+        if (a.exp_mode == kExpAuto) return launch_ring<64, kExpAuto, QMAX>(a, lds, lds_limit, st);
+        if (a.exp_mode == kExpTable) return launch_ring<64, kExpTable, QMAX>(a, lds, lds_limit, st);
+        if (a.exp_mode == kExpShift0) return launch_ring<64, kExpShift0, QMAX>(a, lds, lds_limit, st);
+        return launch_ring<64, kExpShift, QMAX>(a, lds, lds_limit, st);
+    }
+    if (a.exp_mode == kExpAuto) return launch_ring<128, kExpAuto, QMAX>(a, lds, lds_limit, st);
+    if (a.exp_mode == kExpTable) return launch_ring<128, kExpTable, QMAX>(a, lds, lds_limit, st);
+    if (a.exp_mode == kExpShift0) return launch_ring<128, kExpShift0, QMAX>(a, lds, lds_limit, st);
+    return launch_ring<128, kExpShift, QMAX>(a, lds, lds_limit, st);
+}
+}  // namespace
+
 int qflash_launch_fwd_ring(const QflashKernelArgs& a, int lds_limit, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     // everything the kernel's indexing assumes, checked once more where it is launched
-    if (!a.ring_dma || !a.ring || a.bias || a.qmax || a.heads_per_wg != 1 || (a.kv_tile != 64 && a.kv_tile != 128))
+    if (!a.ring_dma || !a.ring || a.bias || a.heads_per_wg != 1 || (a.kv_tile != 64 && a.kv_tile != 128))
         return (int)hipErrorInvalidValue;
     if (a.waves_per_head < 1 || a.waves_per_head > 8 || a.rows_per_wg != 32 * a.waves_per_head) return (int)hipErrorInvalidValue;
     if ((long long)a.rows_per_wg * a.n_qtiles < a.N) return (int)hipErrorInvalidValue;
@@ -185,14 +203,5 @@ int qflash_launch_fwd_ring(const QflashKernelArgs& a, int lds_limit, void* strea
     if (table && a.lut_bytes_max > a.ring_table_lds) return (int)hipErrorInvalidValue;
     const size_t lds = qflash_ring_lds_bytes(a.waves_per_head, a.kv_tile, table ? a.ring_table_lds : 0);
     if (lds > (size_t)lds_limit) return (int)hipErrorInvalidValue;
-    if (a.kv_tile == 64) {
-        if (a.exp_mode == kExpAuto) return launch_ring<64, kExpAuto>(a, lds, lds_limit, st);
-        if (a.exp_mode == kExpTable) return launch_ring<64, kExpTable>(a, lds, lds_limit, st);
-        if (a.exp_mode == kExpShift0) return launch_ring<64, kExpShift0>(a, lds, lds_limit, st);
-        return launch_ring<64, kExpShift>(a, lds, lds_limit, st);
-    }
-    if (a.exp_mode == kExpAuto) return launch_ring<128, kExpAuto>(a, lds, lds_limit, st);
-    if (a.exp_mode == kExpTable) return launch_ring<128, kExpTable>(a, lds, lds_limit, st);
-    if (a.exp_mode == kExpShift0) return launch_ring<128, kExpShift0>(a, lds, lds_limit, st);
-    return launch_ring<128, kExpShift>(a, lds, lds_limit, st);
+    return a.qmax ? launch_variant<true>(a, lds, lds_limit, st) : launch_variant<false>(a, lds, lds_limit, st);
 }
