@@ -202,6 +202,10 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
         // and keep the answers in more scalar registers than there are)
         int N_ = N;
         asm volatile("" : "+s"(N_));
+        // (likewise the lane's half: the key indices of the ragged tile derive from it, two dozen
+        // registers' worth if they are prepared ahead of the loop)
+        int g_ = g;
+        asm volatile("" : "+v"(g_));
         const int n_full = N_ / BC, rem = N_ - n_full * BC;
         const int h = u / nblk, blk = u - h * nblk;
         const int owner = min(h, last_group);
@@ -231,7 +235,7 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
                 qreg[s] = *(lds_v4i*)(size_t)(Qb + row0 * D + (sl.k_off ^ (32 * s)));                      \
         }                                                                                                  \
         process_tile<D, BC, kBiasNone, XM, SB, FULL_, FIRST_, kLaySwizzled, NG_>(                          \
-            st, qreg, nullptr, 0, nullptr, 0, NV_, hc.lut_xp, nullptr, nullptr, c, hc.a_mul, li, g,       \
+            st, qreg, nullptr, 0, nullptr, 0, NV_, hc.lut_xp, nullptr, nullptr, c, hc.a_mul, li, g_,      \
             Kb + 4096 * (J_) + sl.k_off, Vb + 4096 * (J_) + sl.v_off);                                     \
         if (tk == 6) QF_T(9 + (J_))
         // the ragged tile, with its number of groups of 8 keys as a compile-time constant
@@ -257,7 +261,17 @@ __device__ __forceinline__ void cu_body(const QflashKernelArgs& a) {
 #undef QF_TILE
         first_unit = false;
         QF_T(tk + 1);
-        if (i < N) normalise_store<D, 16>(st, a.O + ((size_t)(head0 + h) * N + i) * D, g, a.out_round != 0);
+        if (i < N) {
+            // (uniform base plus a 32-bit lane offset made here: a per-lane 64-bit pointer prepared ahead of
+            // the unit loop would be held in registers across all the tile code, or spilled)
+            v4i w[2];
+            normalise_words<D, 16>(st, a.out_round != 0, w);
+            int8_t* Ob = a.O + (size_t)(head0 + h) * N * D;
+            unsigned o_lane = (unsigned)(i * D + g * (D / 2));
+            asm volatile("" : "+v"(o_lane));
+            *(v4i*)(Ob + o_lane) = w[0];
+            *(v4i*)(Ob + o_lane + 16) = w[1];
+        }
         // next unit
         int nxt = 0;
         if (lane == 0) nxt = __hip_atomic_fetch_add((lds_int*)(size_t)(cnt_base + 4 * 4 * hpw), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
