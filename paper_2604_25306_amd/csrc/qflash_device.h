@@ -24,11 +24,23 @@ struct ExpConst {
     int p_mul_hi_v;          // p_mul << (24 - p_shift): the requantised weight lands in byte 3
 };
 
+// Inline assembly and the matrix pipeline.  A matrix instruction writes its 16 result registers
+// dozens of cycles after it issues, and the compiler inserts the idle cycles that a later vector
+// instruction touching one of them needs -- for the instructions it emits itself, not for the text
+// of an assembly statement.  Two rules keep every statement in these files clear of that window:
+//   - no operand of a statement is a matrix result (results are read by ordinary code first);
+//   - a statement never has a vector register as a pure output.  A pure output may be given any
+//     free register, and a result register whose value happens to be unused (the key groups of a
+//     ragged tile beyond the sequence) counts as free while the matrix instruction that will still
+//     write it is in flight: the late write then destroys the statement's result.  An output tied
+//     to an input ("+v") sits in a register that holds a live value, which cannot be one of those.
+
 // Copy a uniform value into a vector register and keep it there: on this chip a two-operand
-// multiply / max / shift with a scalar source issues slower than with two vector sources.
+// multiply / max / shift with a scalar source issues slower than with two vector sources.  (The
+// copy itself is the compiler's; the empty statement only hides where the value came from.)
 __device__ __forceinline__ int to_vgpr(int v) {
-    int r;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "s"(v));
+    int r = v;
+    asm volatile("" : "+v"(r));
     return r;
 }
 
@@ -46,7 +58,8 @@ __device__ __forceinline__ int shift_exp2(int t, int m, int m2 /* m - 2 s_inv */
         xs2 = t - m2;
     } else {
         const int neg_m = -m;
-        asm("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(xs) : "v"(t), "v"(neg_m), "s"(c.k));
+        xs = t;                                      // (output tied to an input, see above)
+        asm("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(xs) : "v"(neg_m), "s"(c.k));
         xs2 = xs + c.two_s_inv_v;
     }
     const int q = mulhi24(xs, c.M_v);

@@ -439,11 +439,12 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
 // for every u' < 256 l' because u' (R l' - 2^(2L+8)) < 2^(L+8) 2^L.  L = 16 or 20 puts the quotient
 // into byte 1 or 2 of the high product word.  Nearest: floor((2 O + l) / (2 l)), same scheme with
 // numerator 2 O + l and denominator 2 l.
-// min(max(u, 0), hi) for hi >= 0 as one instruction (the median of three).  Inline assembly is safe
-// here: u is the result of an ordinary vector instruction, not of a matrix instruction.
+// min(max(u, 0), hi) for hi >= 0 as one instruction (the median of three).  u is the result of an
+// ordinary vector instruction, not of a matrix instruction, and the output is tied to it (the rules
+// for inline assembly next to to_vgpr).
 __device__ __forceinline__ int clamp_0(int u, int hi) {
-    int r;
-    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(r) : "v"(u), "v"(hi));
+    int r = u;
+    asm("v_med3_i32 %0, %0, 0, %1" : "+v"(r) : "v"(hi));
     return r;
 }
 

@@ -119,3 +119,28 @@ def test_offset_scores_give_the_table_index_in_one_saturating_subtraction():
         assert max(0, sb - edge) == max(0, s - m + x_p) <= x_p
         assert max(0, 0 - edge) == 0
         assert (sb <= mb) and ((-(1 << 21) + (1 << 31)) & M32) <= sb
+
+
+def test_inline_assembly_never_has_a_vector_register_as_a_pure_output():
+    """A pure output ("=v") may be placed in a result register of a matrix instruction that is still
+    in flight (a result nobody reads counts as free), where the compiler adds no idle cycles for
+    an assembly statement and the late result write then destroys the statement's value.  Every
+    vector output in the kernel sources is tied to an input ("+v") instead."""
+    import glob
+    import os
+    import re
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2604_25306_amd", "csrc")
+    files = sorted(glob.glob(os.path.join(csrc, "*.h")) + glob.glob(os.path.join(csrc, "*.hip")) + glob.glob(os.path.join(csrc, "*.cpp")))
+    assert files
+    statements = 0
+    for path in files:
+        text = open(path).read()
+        for m in re.finditer(r"\basm\b(?:\s+volatile)?\s*\(", text):
+            depth, i = 1, m.end()
+            while depth:
+                depth += {"(": 1, ")": -1}.get(text[i], 0)
+                i += 1
+            stmt = text[m.end():i]
+            statements += 1
+            assert '"=v"' not in stmt and '"=&v"' not in stmt, "%s: %s" % (os.path.basename(path), stmt.strip()[:120])
+    assert statements > 10
