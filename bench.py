@@ -279,9 +279,23 @@ def measure_peaks(qf, torch):
     e1.record()
     torch.cuda.synchronize()
     tc = e0.elapsed_time(e1) * 1e-3 / 4
-    return {"mfma_int8_tops": ops / t / 1e12, "mfma_int8_ops_per_clk_cu": ops / t / (clock_ghz * 1e9) / CUS,
+    # vector integer issue: one workgroup of 16 wavefronts per compute unit (4 per SIMD, as the attention kernels run)
+    vout = torch.zeros(2 * CUS + 2, dtype=torch.int64, device=dev)
+    qf.qflash_peaks_valu(CUS, 256, vout)           # warm-up
+    torch.cuda.synchronize()
+    e0.record()
+    lane_ops = qf.qflash_peaks_valu(CUS, 16384, vout)
+    e1.record()
+    torch.cuda.synchronize()
+    tv = e0.elapsed_time(e1) * 1e-3
+    vo = vout.cpu().numpy()[:2 * CUS].reshape(CUS, 2).astype("float64")
+    vclock = float((vo[:, 0] / (vo[:, 1] * 10.0)).mean())
+    return {"valu_lane_tops": lane_ops / tv / 1e12, "valu_clock_ghz": vclock,
+            "valu_cycles_per_instruction_simd": (vclock * 1e9) * tv / (lane_ops / 64.0 / (CUS * 4)),
+            "mfma_int8_tops": ops / t / 1e12, "mfma_int8_ops_per_clk_cu": ops / t / (clock_ghz * 1e9) / CUS,
             "mfma_clock_ghz": clock_ghz, "hbm_copy_gbs": 2.0 * (256 << 20) / tc / 1e9,
-            "how": "512 workgroups x 4 wavefronts x 4096 x 4 independent v_mfma_i32_32x32x32_i8; 256 MiB copy, read + write"}
+            "how": "512 workgroups x 4 wavefronts x 4096 x 4 independent v_mfma_i32_32x32x32_i8; 256 MiB copy, read + write; "
+                   "256 workgroups x 16 wavefronts x 16384 x 16 independent 32-bit integer vector instructions"}
 
 
 def main():
@@ -365,6 +379,7 @@ def main():
         out["roofline"]["frac_of_measured_copy"] = out["roofline"]["achieved"] / pk["hbm_copy_gbs"]
         out["roofline_mfma"]["frac_of_measured_mfma"] = out["roofline_mfma"]["achieved"] / pk["mfma_int8_tops"]
         out["roofline_alu"]["peak_at_measured_clock"] = CUS * LANES_PER_CU_CLK * pk["mfma_clock_ghz"] / 1000.0
+        out["roofline_alu"]["frac_of_measured_valu"] = out["roofline_alu"]["achieved"] / pk["valu_lane_tops"]
 
     # The other benchmark configurations, timed the same way with fewer steps, each checked against
     # the oracle (one pass) unless the baseline is switched off.

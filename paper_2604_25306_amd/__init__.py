@@ -13,5 +13,5 @@ from .binding import (  # noqa: F401
     qflash_destroy, qflash_strerror, EXCLUDED, ERR, CFG_EXP_TABLE, CFG_QUANTISED_MAX,
     MAX_PARAM_HEADS, qflash_packed_bias_bytes, qflash_pack_bias, qflash_attention_packed_bias,
     params_array, PlanInfo, qflash_plan_query, qflash_plan_unit, CacheInfo, qflash_cache_query,
-    WEIGHTS_ARITHMETIC, WEIGHTS_TABLE, WEIGHTS_MIXED, qflash_peaks_mfma_i8, qflash_peaks_copy,
+    WEIGHTS_ARITHMETIC, WEIGHTS_TABLE, WEIGHTS_MIXED, qflash_peaks_mfma_i8, qflash_peaks_copy, qflash_peaks_valu,
 )

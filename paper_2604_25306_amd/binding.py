@@ -22,7 +22,8 @@ EXPORTS = ["qflash_params_from_scales", "qflash_create", "qflash_configure", "qf
            "qflash_plan_query", "qflash_plan_unit", "qflash_cache_query",
            "qflash_destroy", "qflash_strerror"]
 
-PEAKS_EXPORTS = ["qflash_peaks_mfma_i8", "qflash_peaks_mfma_i8_ops", "qflash_peaks_copy"]   # include/qflash_peaks.h
+PEAKS_EXPORTS = ["qflash_peaks_mfma_i8", "qflash_peaks_mfma_i8_ops", "qflash_peaks_copy",
+                 "qflash_peaks_valu", "qflash_peaks_valu_lane_ops"]   # include/qflash_peaks.h
 
 MAX_PARAM_HEADS = 64
 
@@ -126,6 +127,10 @@ def load_library():
         lib.qflash_peaks_mfma_i8.argtypes = [ci, ci, vp, ctypes.c_size_t, vp]
         lib.qflash_peaks_mfma_i8_ops.restype = dbl
         lib.qflash_peaks_mfma_i8_ops.argtypes = [ci, ci]
+        lib.qflash_peaks_valu.restype = ci
+        lib.qflash_peaks_valu.argtypes = [ci, ci, vp, ctypes.c_size_t, vp]
+        lib.qflash_peaks_valu_lane_ops.restype = dbl
+        lib.qflash_peaks_valu_lane_ops.argtypes = [ci, ci]
         lib.qflash_peaks_copy.restype = ci
         lib.qflash_peaks_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.qflash_strerror.restype = ctypes.c_char_p
@@ -369,6 +374,19 @@ def qflash_peaks_mfma_i8(workgroups: int, iters: int, out, stream: Optional[int]
     if rc != 0:
         raise RuntimeError("qflash_peaks_mfma_i8 failed: %d" % rc)
     return float(load_library().qflash_peaks_mfma_i8_ops(int(workgroups), int(iters)))
+
+
+def qflash_peaks_valu(workgroups: int, iters: int, out, stream: Optional[int] = None) -> float:
+    """Enqueue the vector-integer issue-rate kernel; ``out`` as for qflash_peaks_mfma_i8.  Returns the
+    number of lane-operations the launch executes."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(out.device).cuda_stream
+    rc = load_library().qflash_peaks_valu(int(workgroups), int(iters), _ptr(out),
+                                          int(out.numel() * out.element_size()), ctypes.c_void_p(stream))
+    if rc != 0:
+        raise RuntimeError("qflash_peaks_valu failed: %d" % rc)
+    return float(load_library().qflash_peaks_valu_lane_ops(int(workgroups), int(iters)))
 
 
 def qflash_peaks_copy(src, dst, stream: Optional[int] = None) -> None:
