@@ -81,6 +81,24 @@ __device__ __forceinline__ v16i offset_block() {
     for (int v = 0; v < 16; ++v) z[v] = kAccBias;
     return z;
 }
+// Offset of the biased scores of 32-key block kb of a tile, relative to kAccBias.  A matrix
+// instruction takes a constant as its addend only if the constant is one of the few the instruction
+// set has built in (here the bit patterns of 2.0, 4.0, 1.0 and 0.5: 2^30, 2^30 + 2^23, 2^30 - 2^23,
+// 2^30 - 2^24) and, with this compiler, only if no other instruction shares it; a block of sixteen
+// registers filled with the constant costs eight vector and sixteen scalar instructions per tile
+// otherwise.  So each block of a tile gets a constant of its own, and the two places that compare
+// scores across blocks (the row maximum, the table index) take the difference out again.
+__device__ __forceinline__ constexpr int score_offset_delta(int kb) {
+    return kb == 0 ? 0 : kb == 1 ? (1 << 23) : kb == 2 ? -(1 << 23) : -(1 << 24);
+}
+constexpr int kMaskedBiased = 1 << 24;   // a key beyond the sequence, as a biased score at the common offset
+template <int KBI>
+__device__ __forceinline__ v16i score_offset_block() {
+    v16i z;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) z[v] = kAccBias + score_offset_delta(KBI);
+    return z;
+}
 
 // One byte of the weight table.  The table is the first thing in the workgroup's LDS (the resident
 // kernel has no other LDS object, so its dynamic LDS starts at address 0): the index is the address.
@@ -204,6 +222,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
     constexpr int KSTEPS = D / 32, TB = D / 32, KB = BC / 32;
     constexpr bool KZ = XM == kExpShift0;
     static_assert(!SB || (XM == kExpTable && !BIAS), "biased scores: table mode without bias only");
+    static_assert(KB <= 4, "one built-in constant per 32-key block");
     // FULL: the tile has all BC kv rows, every "is this group inside the sequence" test below is
     // true at compile time and the tile is one straight line of code.
     static_assert(NG >= 0 && NG <= BC / 8 && !(FULL && NG != 0), "groups of a ragged tile");
@@ -219,7 +238,9 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         if (blk_on(kb)) {
             const v4i ka0 = LAY == kLaySwizzled ? *(lds_v4i*)(size_t)(kx + 2048 * kb)
                                                 : *(const v4i*)(sK + (32 * kb + li) * KROW + 16 * g);
-            s[kb] = SB ? __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], zb, 0, 0, 0)
+            const v16i zs = kb == 0 ? score_offset_block<0>() : kb == 1 ? score_offset_block<1>()
+                          : kb == 2 ? score_offset_block<2>() : score_offset_block<3>();
+            s[kb] = SB ? __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], zs, 0, 0, 0)
                        : __builtin_amdgcn_mfma_i32_32x32x32_i8(ka0, qreg[0], v16i{0}, 0, 0, 0);
 #pragma unroll
             for (int ks = 1; ks < KSTEPS; ++ks) {
@@ -262,7 +283,9 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                         const int bv = beyond ? INT32_MIN : bias_row[col];
                         val = __builtin_elementwise_add_sat(val, bv);
                     } else if (beyond) {
-                        val = SB ? 0 : kNegBig;   // below every real score in either representation
+                        // below every real score in either representation (biased: 2^24 at the
+                        // common offset, so that taking the block's own offset out cannot wrap)
+                        val = SB ? kMaskedBiased + score_offset_delta(kb) : kNegBig;
                     }
                     s[kb][4 * a4 + b] = val;
                 }
@@ -275,7 +298,7 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         int mk[KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            mk[kb] = kb == 0 ? st.m : (SB ? 0 : INT32_MIN);
+            mk[kb] = kb == 0 ? st.m : (SB ? kMaskedBiased + score_offset_delta(kb) : INT32_MIN);
 #pragma unroll
             for (int a4 = 0; a4 < 4; ++a4)
                 if (grp_on(kb, a4)) {
@@ -285,7 +308,14 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         }
         m_new = mk[0];
 #pragma unroll
-        for (int kb = 1; kb < KB; ++kb) m_new = smax<SB>(m_new, mk[kb]);
+        for (int kb = 1; kb < KB; ++kb) {
+            if (SB) {
+                // (a block that does not exist has no maximum to bring to the common offset)
+                if (blk_on(kb)) m_new = smax<SB>(m_new, (int)((unsigned)mk[kb] - (unsigned)score_offset_delta(kb)));
+            } else {
+                m_new = smax<SB>(m_new, mk[kb]);
+            }
+        }
     }
     {
         const HalfPair hp = both_halves(m_new);
@@ -342,7 +372,8 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
         const unsigned x_p_v = (unsigned)to_vgpr(x_p);
         const unsigned edge = (unsigned)m_new - x_p_v;       // score_biased: m + 2^30 - x_p > 0
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
+        for (int kb = 0; kb < KB; ++kb) {
+            const unsigned edge_kb = edge + (unsigned)score_offset_delta(kb);   // (the block's own offset)
 #pragma unroll
             for (int a4 = 0; a4 < 4; ++a4)
                 if (grp_on(kb, a4)) {
@@ -351,11 +382,12 @@ __device__ __forceinline__ void process_tile(RowState<D>& st, const v4i* qreg, c
                         // Saturating subtractions are fast-class instructions; as builtins, because
                         // they read MFMA results.
                         const unsigned sv = (unsigned)s[kb][4 * a4 + b];
-                        const unsigned idx = SB ? __builtin_elementwise_sub_sat(sv, edge)
+                        const unsigned idx = SB ? __builtin_elementwise_sub_sat(sv, edge_kb)
                                                 : __builtin_elementwise_sub_sat(x_p_v, (unsigned)m_new - sv);
                         s[kb][4 * a4 + b] = table_weight(idx);
                     }
                 }
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (!FIRST) release_past();
         __builtin_amdgcn_sched_barrier(0);
