@@ -136,14 +136,15 @@ int qflash_cache_query(qflash_ctx* ctx, qflash_cache_info* out /* host */);
  *            the rescaling of past accumulators happen per KV tile); it does not depend on the
  *            query block size or on any launch parameter.
  *            Cost: 64 is the tile the kernels are tuned for.  Measured on MI355X: with short
- *            sequences (N <= 256) tile 128 takes 1.2 to 1.3 times the time of tile 64 (ViT-B/16
- *            B=64: 25.5 against 21.4 us; the variant runs short of registers, and the library
+ *            sequences (N <= 256) tile 128 takes 1.3 times the time of tile 64 (ViT-B/16
+ *            B=64: 24.9 against 19.2 us; the variant runs short of registers, and the library
  *            computes its weights arithmetically there because the look-up variant is slower
- *            still); on long sequences with d = 64 it is 4 % faster (N = 577: 44.3 against 46.2 us).  A d = 32 sequence
+ *            still); on long sequences with d = 64 the two are within 1 % (N = 577: 43.7 against
+ *            43.9 us).  A d = 32 sequence
  *            too long for LDS (N above about 1000) takes the streamed kernel, which stages one
  *            tile at a time with two barriers per tile and computes weights arithmetically:
- *            about 0.8 of the ring kernel's rate per score with tile 64 (B*H = 64, N = 2100:
- *            150 us), 0.53 with tile 128 (225 us).
+ *            about 0.65 of the ring kernel's rate per score with tile 64 (B*H = 64, N = 2100:
+ *            150 us), 0.43 with tile 128 (228 us).
  *   p        host; validated on every call.
  *   hip_stream  a hipStream_t of the context's device (NULL = the default stream).
  *
