@@ -121,6 +121,36 @@ def test_offset_scores_give_the_table_index_in_one_saturating_subtraction():
         assert (sb <= mb) and ((-(1 << 21) + (1 << 31)) & M32) <= sb
 
 
+def test_one_offset_per_score_block():
+    """The 32-key blocks of a tile carry the offsets 2^30 + {0, 2^23, -2^23, -2^24} (bit patterns of 2.0, 4.0,
+    1.0, 0.5).  Removing a block's own offset from its maximum and adding it to the table edge gives the
+    index and the maximum of the common offset 2^30; a key beyond the sequence stands at 2^24 above the
+    common offset: below every real score, index 0, and no subtraction wraps."""
+    import struct
+    off = 1 << 30
+    deltas = [0, 1 << 23, -(1 << 23), -(1 << 24)]
+    for d, f in zip(deltas, (2.0, 4.0, 1.0, 0.5)):
+        assert struct.unpack("<I", struct.pack("<f", f))[0] == off + d
+    masked = 1 << 24
+    rng = np.random.default_rng(11)
+    for _ in range(20000):
+        x_p = int(rng.integers(1, 40960))
+        scores = [int(v) for v in rng.integers(-(1 << 21) + 1, 1 << 21, size=4)]
+        m = int(rng.integers(max(scores), 1 << 21))
+        edge = (m + off - x_p) & M32                           # common offset
+        block_max = []
+        for s, d in zip(scores, deltas):
+            sb = (s + off + d) & M32                           # what the product leaves in the block
+            edge_kb = (edge + d) & M32
+            assert max(0, sb - edge_kb) == max(0, s - m + x_p)
+            mb = (masked + d) & M32                            # a key beyond the sequence
+            assert 0 <= masked + d < (1 << 32) and max(0, mb - edge_kb) == 0
+            assert mb < sb
+            block_max.append(((max(sb, mb) - d) & M32))        # the block's maximum at the common offset
+        assert max(block_max) == max(scores) + off
+        assert all(((masked + d) - d) & M32 == masked for d in deltas)
+
+
 def test_inline_assembly_never_has_a_vector_register_as_a_pure_output():
     """A pure output ("=v") may be placed in a result register of a matrix instruction that is still
     in flight (a result nobody reads counts as free), where the compiler adds no idle cycles for
